@@ -1,0 +1,146 @@
+/*
+ * moe_wq.h - C ABI of the MI355X (gfx950) sparsely activated expert FFN layer with
+ * weight-only int4/int8 quantised experts (arXiv 2211.10017, Sec. 3.3 "Optimized GPU kernel
+ * design" and Sec. 3.4 "Expert quantization with 4-bit and 8-bit").
+ *
+ * The layer is five calls, made in this order on one stream:
+ *
+ *   moe_quantize_experts   offline, once per weight tensor
+ *   moe_gate_topk -> moe_permute -> moe_grouped_ffn_wq -> moe_combine     per layer call
+ *
+ * Conventions common to every entry point
+ *   - Every pointer is a DEVICE pointer unless it says otherwise.  The caller allocates and
+ *     owns every buffer; the library never allocates, frees or keeps device memory between
+ *     calls.  Scratch comes from a caller-provided workspace sized by the *_workspace_bytes
+ *     queries (pure host functions).  Buffers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
+ *     enqueued on it; no entry point synchronises with the host or reads device memory from
+ *     the host (the per-expert offsets stay on the device).
+ *   - Return value: MOE_OK or one of the MOE_ERR_* codes.  Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued, and
+ *     moe_last_error() returns a thread-local message.  No exceptions, no aborts.
+ *   - Identical inputs give bit-identical outputs (no floating-point atomics, stable sort).
+ *   - Notation: T tokens, d = d_model, F = d_ff, E experts, k experts per token,
+ *     R = T*k routed rows, assignment id a = t*k + j.  Expert weights are (E, K, N)
+ *     row-major with N contiguous, so that a GEMM is A[m x K] @ B[K x N] (Table 1 caption):
+ *     fc1 has K = d, N = F; fc2 has K = F, N = d.
+ */
+#ifndef MOE_WQ_H
+#define MOE_WQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1,   /* null pointer, non-positive or misaligned dimension, k > E ... */
+    MOE_ERR_UNSUPPORTED = 2,   /* bits not in {4,8}, unknown dtype, E above the supported range */
+    MOE_ERR_WORKSPACE = 3,     /* workspace missing or smaller than the query says */
+    MOE_ERR_HIP = 4            /* a launch failed (hipGetLastError) */
+};
+
+/* element types of activation-like tensors */
+enum { MOE_F16 = 0, MOE_BF16 = 1, MOE_F32 = 2 };
+
+/* Message for the last error returned on this thread ("" if none). */
+const char *moe_last_error(void);
+
+/* Library ABI version (bumped when a signature or the packed layout changes). */
+int moe_abi_version(void);
+
+/*
+ * Sec. 3.4: symmetric, range-based quantisation of expert weights, one fp16 scale per output
+ * channel n (the paper's (E,1,N) scales for (E,M,N) weights), or per group of `group_size`
+ * rows along K.  qmax = 127 (8 bits) / 7 (4 bits); scale = fp16(absmax / qmax);
+ * code = clamp(round_half_even(w / scale), -qmax, qmax); an all-zero channel has scale 0 and
+ * codes 0.  Dequantisation (Algorithm 1) is code * scale.
+ *
+ *   w          [E,K,N] fp32
+ *   bits       4 or 8
+ *   group_size 0 or K: per channel; otherwise must divide K and be a multiple of 64
+ *   q_canon    interchange codes: bits=8: int8 [E,K,N]; bits=4: [E,K,N/2] bytes, two's-complement
+ *              nibbles, even n in the low nibble.  May be NULL.
+ *   scales     fp16 [E, K/group_size, N]
+ *   q_packed   the layout moe_grouped_ffn_wq reads: same byte count as q_canon, codes stored
+ *              offset-binary (+128 / +8, Sec. 3.4.1) and pre-shuffled into per-wavefront MFMA
+ *              operand order; opaque to the caller.  May be NULL.
+ * Requires N % 32 == 0 and K % 64 == 0.  E may be a slice: calling once per expert with E = 1
+ * and offset pointers gives the same bytes as one call over all experts.
+ */
+int moe_quantize_experts(const float *w, int E, int K, int N, int bits, int group_size,
+                         void *q_canon, void *scales, void *q_packed, void *stream);
+
+/*
+ * Sec. 3.3: the top-k gating function.  logit[t,e] = sum_i x[t,i]*wg[i,e] (+ bias[e]); the k
+ * largest logits win (ties: lower expert index; slots in descending logit order);
+ * expert_scale is the softmax probability (over all E logits, fp32) of each chosen expert,
+ * divided by the sum of the k chosen probabilities when renormalize != 0 and k > 1.
+ * The logit is accumulated in fp32 as four partial sums (128-element blocks of i dealt
+ * round-robin to the four sums, each in increasing i), combined as ((p0+p1)+p2)+p3, then
+ * the bias is added: this order is part of the contract, so routing is reproducible.
+ *
+ *   x [T,d] act_dtype (MOE_F16 | MOE_BF16), wg [d,E] same dtype, bias [E] fp32 or NULL
+ *   expert_idx [T,k] int32, expert_scale [T,k] fp32
+ * Requires 1 <= k <= 2, k <= E <= 256, d >= 1.
+ */
+int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias, int T, int d,
+                  int E, int k, int renormalize, int32_t *expert_idx, float *expert_scale,
+                  void *stream);
+
+/*
+ * Sec. 3.3: routing.  The (expert, row) tuples are sorted by expert with a stable counting
+ * sort and the activation rows are gathered into expert-contiguous order.
+ *
+ *   expert_idx [T,k]; x [T,d] act_dtype
+ *   x_perm [R,d]          x_perm[r] = x[perm_src[r] / k]
+ *   perm_src [R]          assignment id held by sorted position r
+ *   inv_perm [R]          sorted position of assignment a
+ *   expert_offsets [E+1]  rows of expert e are offsets[e] .. offsets[e+1]-1  (start of each
+ *                         expert's sub-matrix); stays on the device
+ * Entries of expert_idx outside [0,E) are a caller error (not checked).  d % 8 == 0.
+ */
+size_t moe_permute_workspace_bytes(int T, int k, int E);
+int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, int k, int E,
+                int d, void *x_perm, int32_t *perm_src, int32_t *inv_perm,
+                int32_t *expert_offsets, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Sec. 3.3 (grouped GEMM, Fig. 1) + Sec. 3.4 (dequantisation fused into the GEMM): for every
+ * expert e and each of its rows r,
+ *     h[r] = relu(x_perm[r] @ deq(W1[e]) + b1[e])   stored in act_dtype
+ *     y[r] = h[r] @ deq(W2[e]) + b2[e]              stored in y_dtype
+ * with fp16 MFMA and fp32 accumulation; the packed codes are unpacked and dequantised in
+ * registers (never written back to memory).  Experts without rows cost no weight traffic.
+ *
+ *   x_perm [R,d] act_dtype; expert_offsets [E+1]
+ *   w1_packed / w2_packed: q_packed from moe_quantize_experts for (E,d,F) / (E,F,d)
+ *   s1 fp16 [E, d/g, F]; s2 fp16 [E, F/g, d]  (g = group_size, or K when group_size is 0)
+ *   b1 [E,F] / b2 [E,d] fp16 or NULL
+ *   y_perm [R,d] in y_dtype (MOE_F16 | MOE_BF16 | MOE_F32)
+ * Requires d % 64 == 0, F % 64 == 0, bits in {4,8}, group_size 0 or a multiple of 64 dividing
+ * both d and F.
+ */
+size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E, int act_dtype);
+int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
+                       int E, int d, int F, int bits, int group_size, const void *w1_packed,
+                       const void *s1, const void *b1, const void *w2_packed, const void *s2,
+                       const void *b2, void *y_perm, int y_dtype, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Sec. 3.3, last step: rows return to their original order and are multiplied by
+ * expert_scale:  out[t] = sum_j expert_scale[t,j] * y_perm[inv_perm[t*k+j]]  (fp32, j ascending).
+ *   y_perm [R,d] y_dtype; out [T,d] out_dtype (each MOE_F16 | MOE_BF16 | MOE_F32); d % 8 == 0.
+ */
+int moe_combine(const void *y_perm, int y_dtype, const int32_t *inv_perm,
+                const float *expert_scale, int T, int k, int d, void *out, int out_dtype,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_WQ_H */

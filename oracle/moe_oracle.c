@@ -115,16 +115,20 @@ void orc_quantize(const float *w, int E, int K, int N, int bits, int g,
         for (int gi = 0; gi < G; ++gi) {
             const float *we = w + (size_t)e * K * N;
             int8_t *qe = q + (size_t)e * K * N;
-            for (int n = 0; n < N; ++n) {
-                float amax = 0.0f;
-                for (int m = gi * g; m < (gi + 1) * g; ++m) {
+            uint16_t *se = s_bits + ((size_t)e * G + gi) * N;
+            float *amax = (float *)calloc((size_t)N, sizeof(float));
+            for (int m = gi * g; m < (gi + 1) * g; ++m)          /* range of each channel */
+                for (int n = 0; n < N; ++n) {
                     float a = fabsf(we[(size_t)m * N + n]);
-                    if (a > amax) amax = a;
+                    if (a > amax[n]) amax[n] = a;
                 }
-                uint16_t sb = orc_f32_to_f16_bits(amax / (float)qmax);
-                float s = orc_f16_bits_to_f32(sb);
-                s_bits[((size_t)e * G + gi) * N + n] = sb;
-                for (int m = gi * g; m < (gi + 1) * g; ++m) {
+            for (int n = 0; n < N; ++n) {
+                se[n] = orc_f32_to_f16_bits(amax[n] / (float)qmax);
+                amax[n] = orc_f16_bits_to_f32(se[n]);            /* now the stored scale */
+            }
+            for (int m = gi * g; m < (gi + 1) * g; ++m)
+                for (int n = 0; n < N; ++n) {
+                    float s = amax[n];
                     float c = 0.0f;
                     if (s != 0.0f) {
                         c = nearbyintf(we[(size_t)m * N + n] / s);
@@ -133,7 +137,7 @@ void orc_quantize(const float *w, int E, int K, int N, int bits, int g,
                     }
                     qe[(size_t)m * N + n] = (int8_t)c;
                 }
-            }
+            free(amax);
         }
 }
 
@@ -162,12 +166,16 @@ void orc_dequantize(const int8_t *q, const uint16_t *s_bits, int E, int K, int N
     const int G = K / g;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int e = 0; e < E; ++e)
-        for (int m = 0; m < K; ++m)
-            for (int n = 0; n < N; ++n) {
-                float f = (float)q[((size_t)e * K + m) * N + n];
-                float s = orc_f16_bits_to_f32(s_bits[((size_t)e * G + m / g) * N + n]);
-                wdq[((size_t)e * K + m) * N + n] = f * s;
-            }
+        for (int gi = 0; gi < G; ++gi) {
+            float *sf = (float *)malloc(sizeof(float) * (size_t)N);
+            for (int n = 0; n < N; ++n) sf[n] = orc_f16_bits_to_f32(s_bits[((size_t)e * G + gi) * N + n]);
+            for (int m = gi * g; m < (gi + 1) * g; ++m)
+                for (int n = 0; n < N; ++n) {
+                    float f = (float)q[((size_t)e * K + m) * N + n];      /* IntToFloat */
+                    wdq[((size_t)e * K + m) * N + n] = f * sf[n];
+                }
+            free(sf);
+        }
 }
 
 /* Sec. 3.4.1-3.4.3: integer-to-FP16 conversion without an I2F instruction.  The code is

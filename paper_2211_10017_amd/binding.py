@@ -1,0 +1,183 @@
+"""Thin ctypes binding of the C-ABI HIP library (include/moe_wq.h).
+
+Argument marshalling only: every function takes torch CUDA tensors, checks their dtype,
+device and contiguity, and passes raw device pointers plus the current stream.  No step of
+the layer runs in Python or in torch ops.  If the library has not been built the first call
+raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_wq.so")
+
+MOE_F16, MOE_BF16, MOE_F32 = 0, 1, 2
+_DT = {torch.float16: MOE_F16, torch.bfloat16: MOE_BF16, torch.float32: MOE_F32}
+
+EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
+           "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
+           "moe_grouped_ffn_wq", "moe_combine"]
+
+_lib = None
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+def load():
+    """Load libmoe_wq.so (once) and declare the signatures of include/moe_wq.h."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise MoeError("HIP library %s is missing: build it with "
+                       "`python -m paper_2211_10017_amd.build` (no fallback exists)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_last_error.argtypes = []
+    lib.moe_abi_version.restype = i
+    lib.moe_quantize_experts.restype = i
+    lib.moe_quantize_experts.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp]
+    lib.moe_gate_topk.restype = i
+    lib.moe_gate_topk.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp, vp]
+    lib.moe_permute_workspace_bytes.restype = sz
+    lib.moe_permute_workspace_bytes.argtypes = [i, i, i]
+    lib.moe_permute.restype = i
+    lib.moe_permute.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_grouped_ffn_wq_workspace_bytes.restype = sz
+    lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
+    lib.moe_grouped_ffn_wq.restype = i
+    lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_combine.restype = i
+    lib.moe_combine.argtypes = [vp, i, vp, vp, i, i, i, vp, i, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MoeError("%s failed (code %d): %s" % (what, rc, load().moe_last_error().decode()))
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise MoeError("%s must be a contiguous CUDA tensor" % name)
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise MoeError("%s has dtype %s, expected %s" % (name, t.dtype, dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def moe_quantize_experts(w, bits: int, group_size: int = 0, want_canon: bool = True,
+                         want_packed: bool = True):
+    """w fp32 [E,K,N] -> (q_canon uint8/int8, scales fp16 [E,K/g,N], q_packed uint8)."""
+    E, K, N = w.shape
+    g = K if group_size in (0, K) else group_size
+    dev = w.device
+    nbytes = E * K * N * bits // 8
+    q_canon = None
+    if want_canon:
+        q_canon = (torch.empty((E, K, N), dtype=torch.int8, device=dev) if bits == 8
+                   else torch.empty((E, K, N // 2), dtype=torch.uint8, device=dev))
+    scales = torch.empty((E, K // g, N), dtype=torch.float16, device=dev)
+    q_packed = torch.empty(nbytes, dtype=torch.uint8, device=dev) if want_packed else None
+    rc = load().moe_quantize_experts(_ptr(w, torch.float32, "w"), E, K, N, bits, group_size,
+                                     _ptr(q_canon), _ptr(scales), _ptr(q_packed), _stream())
+    _check(rc, "moe_quantize_experts")
+    return q_canon, scales, q_packed
+
+
+def moe_quantize_experts_into(w, bits, group_size, q_canon, scales, q_packed):
+    """Same call writing into caller-provided slices (for expert-at-a-time quantisation)."""
+    E, K, N = w.shape
+    rc = load().moe_quantize_experts(_ptr(w, torch.float32, "w"), E, K, N, bits, group_size,
+                                     _ptr(q_canon), _ptr(scales, torch.float16), _ptr(q_packed), _stream())
+    _check(rc, "moe_quantize_experts")
+
+
+def moe_gate_topk(x, wg, bias, k: int, renormalize: bool = True, out=None):
+    T, d = x.shape
+    E = wg.shape[1]
+    if wg.dtype != x.dtype or wg.shape[0] != d:
+        raise MoeError("wg must be [d,E] in the dtype of x")
+    if out is None:
+        idx = torch.empty((T, k), dtype=torch.int32, device=x.device)
+        scale = torch.empty((T, k), dtype=torch.float32, device=x.device)
+    else:
+        idx, scale = out
+    rc = load().moe_gate_topk(_ptr(x, (torch.float16, torch.bfloat16), "x"), _DT[x.dtype], _ptr(wg),
+                              _ptr(bias, torch.float32, "bias"), T, d, E, k, int(renormalize),
+                              _ptr(idx, torch.int32), _ptr(scale, torch.float32), _stream())
+    _check(rc, "moe_gate_topk")
+    return idx, scale
+
+
+def moe_permute_workspace_bytes(T: int, k: int, E: int) -> int:
+    return int(load().moe_permute_workspace_bytes(T, k, E))
+
+
+def moe_permute(expert_idx, x, E: int, out=None, workspace=None):
+    T, k = expert_idx.shape
+    d = x.shape[1]
+    R = T * k
+    dev = x.device
+    if out is None:
+        x_perm = torch.empty((R, d), dtype=x.dtype, device=dev)
+        perm_src = torch.empty(R, dtype=torch.int32, device=dev)
+        inv_perm = torch.empty(R, dtype=torch.int32, device=dev)
+        offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    else:
+        x_perm, perm_src, inv_perm, offsets = out
+    if workspace is None:
+        workspace = torch.empty(moe_permute_workspace_bytes(T, k, E), dtype=torch.uint8, device=dev)
+    rc = load().moe_permute(_ptr(expert_idx, torch.int32, "expert_idx"), _ptr(x), _DT[x.dtype], T, k, E, d,
+                            _ptr(x_perm), _ptr(perm_src, torch.int32), _ptr(inv_perm, torch.int32),
+                            _ptr(offsets, torch.int32), _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moe_permute")
+    return x_perm, perm_src, inv_perm, offsets
+
+
+def moe_grouped_ffn_wq_workspace_bytes(R: int, d: int, F: int, E: int, act_dtype) -> int:
+    return int(load().moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, _DT[act_dtype]))
+
+
+def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
+                       w1_packed, s1, w2_packed, s2, b1=None, b2=None, y_dtype=None, y_perm=None,
+                       workspace=None):
+    R = x_perm.shape[0]
+    y_dtype = y_dtype or x_perm.dtype
+    if y_perm is None:
+        y_perm = torch.empty((R, d), dtype=y_dtype, device=x_perm.device)
+    if workspace is None:
+        workspace = torch.empty(moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, x_perm.dtype),
+                                dtype=torch.uint8, device=x_perm.device)
+    rc = load().moe_grouped_ffn_wq(
+        _ptr(x_perm, (torch.float16, torch.bfloat16), "x_perm"), _DT[x_perm.dtype],
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E, d, F, bits, group_size,
+        _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"), _ptr(b1, torch.float16, "b1"),
+        _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"), _ptr(b2, torch.float16, "b2"),
+        _ptr(y_perm), _DT[y_perm.dtype], _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moe_grouped_ffn_wq")
+    return y_perm
+
+
+def moe_combine(y_perm, inv_perm, expert_scale, T: int, k: int, out_dtype=torch.float32, out=None):
+    d = y_perm.shape[1]
+    if out is None:
+        out = torch.empty((T, d), dtype=out_dtype, device=y_perm.device)
+    rc = load().moe_combine(_ptr(y_perm), _DT[y_perm.dtype], _ptr(inv_perm, torch.int32, "inv_perm"),
+                            _ptr(expert_scale, torch.float32, "expert_scale"), T, k, d, _ptr(out),
+                            _DT[out.dtype], _stream())
+    _check(rc, "moe_combine")
+    return out

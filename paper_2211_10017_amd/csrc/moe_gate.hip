@@ -1,0 +1,187 @@
+// moe_gate_topk: router logits, top-k selection and gate probabilities (Sec. 3.3).
+//
+// Mapping: a lane owns one expert (NE experts when E > 64) for TB tokens; when E < 64 a
+// wavefront is cut into 64/EL token groups of EL = pow2ceil(E) lanes.  The four wavefronts of
+// a block take the four partial sums of the contract (128-element blocks of the feature axis
+// dealt round-robin), so the floating-point order is fixed by the definition, not by the
+// launch shape.  Softmax and top-k are butterfly reductions over the EL lanes of a group.
+#include <math.h>
+
+#include "moe_common.h"
+
+namespace moe {
+
+constexpr int kGateTB = 4;       // tokens per lane group
+constexpr int kGateBlk = 128;    // feature block of one partial-sum turn
+
+template <bool BF16>
+__device__ inline float act_to_float(uint16_t v)
+{
+    if (BF16) return __uint_as_float((uint32_t)v << 16);
+    __half h;
+    *reinterpret_cast<uint16_t *>(&h) = v;
+    return __half2float(h);
+}
+
+template <bool BF16, int NE>
+__global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ x,
+                                                   const uint16_t *__restrict__ wg,
+                                                   const float *__restrict__ bias, int T, int d,
+                                                   int E, int EL, int k, int renorm,
+                                                   int32_t *__restrict__ expert_idx,
+                                                   float *__restrict__ expert_scale)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int G = 64 / EL;                        // token groups per wavefront
+    const int grp = lane / EL, le = lane % EL;
+    const int ntok = G * kGateTB;                 // tokens per block
+    const int t0 = blockIdx.x * ntok;
+
+    // wave-private staging area for x: [ntok][128] 16-bit values
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * ntok * kGateBlk;
+    float *part = reinterpret_cast<float *>(smem + (size_t)4 * ntok * kGateBlk * 2);  // [4][NE][TB][64]
+
+    float acc[NE][kGateTB];
+#pragma unroll
+    for (int a = 0; a < NE; ++a)
+#pragma unroll
+        for (int b = 0; b < kGateTB; ++b) acc[a][b] = 0.0f;
+
+    const int nblk = (d + kGateBlk - 1) / kGateBlk;
+    const int turns = (nblk + 3) / 4;             // same trip count for all four wavefronts
+    for (int turn = 0; turn < turns; ++turn) {
+        const int blk = turn * 4 + wave;
+        const int i0 = blk * kGateBlk;
+        const int lim = blk < nblk ? min(kGateBlk, d - i0) : 0;     // multiple of 8
+        // stage x[t0 .. t0+ntok)[i0 .. i0+lim): 16 lanes per row, 16 bytes per lane
+        for (int row = lane >> 4; row < ntok; row += 4) {
+            const int seg = (lane & 15) * 8;
+            const int t = min(t0 + row, T - 1);
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (seg < lim) v = *reinterpret_cast<const uint4 *>(x + (size_t)t * d + i0 + seg);
+            *reinterpret_cast<uint4 *>(xs + row * kGateBlk + seg) = v;
+        }
+        __syncthreads();
+        for (int i = 0; i < lim; i += 8) {
+            float wv[NE][8];
+#pragma unroll
+            for (int a = 0; a < NE; ++a) {
+                const int e = min(a * 64 + le, E - 1);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>(wg[(size_t)(i0 + i + u) * E + e]);
+            }
+#pragma unroll
+            for (int b = 0; b < kGateTB; ++b) {
+                const uint4 raw = *reinterpret_cast<const uint4 *>(xs + (grp * kGateTB + b) * kGateBlk + i);
+                const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float xv = act_to_float<BF16>((uint16_t)(r[u >> 1] >> (16 * (u & 1))));
+#pragma unroll
+                    for (int a = 0; a < NE; ++a) acc[a][b] = fmaf(xv, wv[a][u], acc[a][b]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int a = 0; a < NE; ++a)
+#pragma unroll
+        for (int b = 0; b < kGateTB; ++b) part[((wave * NE + a) * kGateTB + b) * 64 + lane] = acc[a][b];
+    __syncthreads();
+
+    // wavefront `wave` finishes token slot b = wave of every group
+    const int b = wave;
+    const int t = t0 + grp * kGateTB + b;
+    float lg[NE];
+    const float NEG = -INFINITY;
+#pragma unroll
+    for (int a = 0; a < NE; ++a) {
+        const int e = a * 64 + le;
+        float p0 = part[((0 * NE + a) * kGateTB + b) * 64 + lane];
+        float p1 = part[((1 * NE + a) * kGateTB + b) * 64 + lane];
+        float p2 = part[((2 * NE + a) * kGateTB + b) * 64 + lane];
+        float p3 = part[((3 * NE + a) * kGateTB + b) * 64 + lane];
+        float l = ((p0 + p1) + p2) + p3;
+        if (e < E && bias) l = l + bias[e];
+        lg[a] = e < E ? l : NEG;
+    }
+
+    // best (value, index) with ties to the lower index
+    int sel[2] = {0, 0};
+    float selv[2] = {0.0f, 0.0f};
+    for (int j = 0; j < k; ++j) {
+        float bv = NEG;
+        int be = 0x7fffffff;
+#pragma unroll
+        for (int a = 0; a < NE; ++a) {
+            const int e = a * 64 + le;
+            const bool taken = j == 1 && e == sel[0];
+            if (e < E && !taken && (lg[a] > bv || be == 0x7fffffff)) { bv = lg[a]; be = e; }
+        }
+        for (int off = EL >> 1; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oe = __shfl_xor(be, off);
+            if (oe != 0x7fffffff && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be))) { bv = ov; be = oe; }
+        }
+        sel[j] = be;
+        selv[j] = bv;
+    }
+    const float lmax = selv[0];
+    float den = 0.0f;
+#pragma unroll
+    for (int a = 0; a < NE; ++a)
+        if (a * 64 + le < E) den += expf(lg[a] - lmax);
+    for (int off = EL >> 1; off > 0; off >>= 1) den += __shfl_xor(den, off);
+
+    if (le == 0 && t < T) {
+        if (k == 1) {
+            expert_idx[t] = sel[0];
+            expert_scale[t] = 1.0f / den;
+        } else {
+            const float e2 = expf(selv[1] - lmax);
+            float s0 = 1.0f / den, s1 = e2 / den;
+            if (renorm) { s0 = 1.0f / (1.0f + e2); s1 = e2 / (1.0f + e2); }
+            expert_idx[2 * t] = sel[0];
+            expert_idx[2 * t + 1] = sel[1];
+            expert_scale[2 * t] = s0;
+            expert_scale[2 * t + 1] = s1;
+        }
+    }
+}
+
+}  // namespace moe
+
+extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias, int T,
+                             int d, int E, int k, int renormalize, int32_t *expert_idx,
+                             float *expert_scale, void *stream)
+{
+    using namespace moe;
+    if (!x || !wg || !expert_idx || !expert_scale) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: NULL pointer");
+    if (T < 0 || d <= 0 || E <= 0) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: T >= 0, d > 0, E > 0 required");
+    if (d % 8) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: d %% 8 != 0 (d=%d)", d);
+    if (k < 1 || k > 2 || k > E) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: k must be 1 or 2 and <= E (k=%d E=%d)", k, E);
+    if (E > 256) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: E=%d above 256", E);
+    if (act_dtype != MOE_F16 && act_dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: act_dtype must be fp16 or bf16");
+    if (!aligned16(x)) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: x must be 16-byte aligned");
+    if (T == 0) return MOE_OK;
+    int EL = 8;
+    while (EL < E && EL < 64) EL *= 2;
+    const int NE = (E + 63) / 64;
+    const int ntok = (64 / EL) * kGateTB;
+    const size_t smem = (size_t)4 * ntok * kGateBlk * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * kGateTB * 64 * 4;
+    dim3 grid((T + ntok - 1) / ntok), block(256);
+    const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
+    hipStream_t s = as_stream(stream);
+#define MOE_GATE_LAUNCH(BF, NEV)                                                                  \
+    hipLaunchKernelGGL((gate_kernel<BF, NEV>), grid, block, smem, s, xp, wp, bias, T, d, E, EL, k, \
+                       renormalize, expert_idx, expert_scale)
+    const bool bf = act_dtype == MOE_BF16;
+    if (NE == 1) { if (bf) MOE_GATE_LAUNCH(true, 1); else MOE_GATE_LAUNCH(false, 1); }
+    else if (NE == 2) { if (bf) MOE_GATE_LAUNCH(true, 2); else MOE_GATE_LAUNCH(false, 2); }
+    else { if (bf) MOE_GATE_LAUNCH(true, 4); else MOE_GATE_LAUNCH(false, 4); }
+#undef MOE_GATE_LAUNCH
+    return check_launch("moe_gate_topk");
+}

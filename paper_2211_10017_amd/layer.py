@@ -1,0 +1,78 @@
+"""MoEExpertLayer: owns the device buffers of one expert FFN layer and chains the five C-ABI
+calls (Sec. 3.3: gate -> permute -> grouped GEMM pair -> un-permute/scale).  It allocates
+every buffer once; forward() only marshals pointers, so it can run in a tight loop."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class MoEExpertLayer:
+    def __init__(self, T, d, F, E, k, bits, group_size=0, act_dtype=torch.float16, renormalize=True,
+                 y_dtype=None, out_dtype=torch.float32, device="cuda:0"):
+        self.T, self.d, self.F, self.E, self.k = T, d, F, E, k
+        self.bits, self.group_size, self.renormalize = bits, group_size, renormalize
+        self.act_dtype, self.out_dtype = act_dtype, out_dtype
+        # y_perm is kept in fp32 for bf16 activations: an 8-bit significand on y would cost
+        # more than the layer's whole error budget
+        self.y_dtype = y_dtype or (torch.float32 if act_dtype == torch.bfloat16 else act_dtype)
+        dev = self.device = torch.device(device)
+        R = self.R = T * k
+        g1 = d if group_size in (0, d) else group_size
+        g2 = F if group_size in (0, F) else group_size
+        self.bytes1 = d * F * bits // 8
+        self.w1_packed = torch.empty(E * self.bytes1, dtype=torch.uint8, device=dev)
+        self.w2_packed = torch.empty(E * self.bytes1, dtype=torch.uint8, device=dev)
+        self.s1 = torch.empty((E, d // g1, F), dtype=torch.float16, device=dev)
+        self.s2 = torch.empty((E, F // g2, d), dtype=torch.float16, device=dev)
+        self.wg = torch.empty((d, E), dtype=act_dtype, device=dev)
+        self.gate_bias = None
+        self.b1 = self.b2 = None
+        # per-call buffers
+        self.expert_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        self.expert_scale = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.x_perm = torch.empty((R, d), dtype=act_dtype, device=dev)
+        self.perm_src = torch.empty(R, dtype=torch.int32, device=dev)
+        self.inv_perm = torch.empty(R, dtype=torch.int32, device=dev)
+        self.expert_offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+        self.y_perm = torch.empty((R, d), dtype=self.y_dtype, device=dev)
+        self.out = torch.empty((T, d), dtype=out_dtype, device=dev)
+        self.ws_permute = torch.empty(B.moe_permute_workspace_bytes(T, k, E), dtype=torch.uint8, device=dev)
+        self.ws_ffn = torch.empty(B.moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype),
+                                  dtype=torch.uint8, device=dev)
+
+    # -- offline: quantise one expert matrix from its fp32 master (which = 1 | 2) ------------
+    def load_expert(self, which: int, e: int, w_fp32, q_canon_out=None):
+        packed = self.w1_packed if which == 1 else self.w2_packed
+        scales = self.s1 if which == 1 else self.s2
+        B.moe_quantize_experts_into(w_fp32.unsqueeze(0), self.bits, self.group_size, q_canon_out,
+                                    scales[e:e + 1], packed[e * self.bytes1:(e + 1) * self.bytes1])
+
+    def share_weights_from(self, other: "MoEExpertLayer"):
+        for name in ("w1_packed", "w2_packed", "s1", "s2"):
+            setattr(self, name, getattr(other, name))
+
+    # -- per call ---------------------------------------------------------------------------
+    def gate(self, x):
+        return B.moe_gate_topk(x, self.wg, self.gate_bias, self.k, self.renormalize,
+                               out=(self.expert_idx, self.expert_scale))
+
+    def permute(self, x):
+        return B.moe_permute(self.expert_idx, x, self.E,
+                             out=(self.x_perm, self.perm_src, self.inv_perm, self.expert_offsets),
+                             workspace=self.ws_permute)
+
+    def ffn(self):
+        return B.moe_grouped_ffn_wq(self.x_perm, self.expert_offsets, self.E, self.d, self.F, self.bits,
+                                    self.group_size, self.w1_packed, self.s1, self.w2_packed, self.s2,
+                                    self.b1, self.b2, y_perm=self.y_perm, workspace=self.ws_ffn)
+
+    def combine(self):
+        return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out)
+
+    def forward(self, x):
+        self.gate(x)
+        self.permute(x)
+        self.ffn()
+        return self.combine()

@@ -119,6 +119,16 @@ def expert_weight(w: Workload, which: int, e: int) -> np.ndarray:
     return a
 
 
+def expert_weight_batches(w: Workload, which: int, batch: int = 8, threads: int = 8):
+    """Yields (first_expert, [masters...]) for consecutive experts, drawn by a thread pool
+    (each expert has its own stream, so the result does not depend on the batching)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        for e0 in range(0, w.E, batch):
+            es = list(range(e0, min(e0 + batch, w.E)))
+            yield e0, list(pool.map(lambda e: expert_weight(w, which, e), es))
+
+
 def expert_weights(w: Workload, which: int) -> np.ndarray:
     """All experts of one matrix, [E, K, N] float32 (use only when it fits in host memory)."""
     return np.stack([expert_weight(w, which, e) for e in range(w.E)])

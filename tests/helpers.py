@@ -1,0 +1,92 @@
+"""Shared set-up for the GPU parity tests: builds a layer on the device from a seeded
+workload, quantising through the HIP entry point, and the same quantised weights through the
+oracle, comparing the two byte for byte on the way."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2211_10017_amd import MoEExpertLayer
+from paper_2211_10017_amd import workloads as W
+
+TORCH_DT = {"f16": torch.float16, "bf16": torch.bfloat16}
+ORC_DT = {"f16": oracle.F16, "bf16": oracle.BF16}
+
+MAX_ABS_TOL = 2e-2      # the acceptance bounds of the layer output against the oracle
+REL_L2_TOL = 1e-3
+
+
+def to_dev(a: np.ndarray, dtype, device="cuda:0"):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device=device, dtype=dtype)
+
+
+class Prepared:
+    """Device layer + the oracle's view of the same inputs."""
+
+    def __init__(self, w: W.Workload, device="cuda:0", batch=8, keep_oracle_weights=True):
+        self.w = w
+        self.layer = MoEExpertLayer(w.T, w.d, w.F, w.E, w.k, w.bits, w.group_size,
+                                    act_dtype=TORCH_DT[w.act], renormalize=w.renormalize, device=device)
+        self.x = W.activations(w)
+        self.wg = W.gate_weight(w)
+        self.bias = W.gate_bias(w)
+        self.layer.wg.copy_(to_dev(self.wg, TORCH_DT[w.act], device))
+        if self.bias is not None:
+            self.layer.gate_bias = to_dev(self.bias, torch.float32, device)
+        self.x_dev = to_dev(self.x, TORCH_DT[w.act], device)
+        self.quant_mismatches = 0
+        self.q = {1: None, 2: None}
+        self.s = {1: None, 2: None}
+        for which in (1, 2):
+            K, N = (w.d, w.F) if which == 1 else (w.F, w.d)
+            g = K if w.group_size in (0, K) else w.group_size
+            if keep_oracle_weights:
+                self.q[which] = np.empty((w.E, K, N), dtype=np.int8)
+                self.s[which] = np.empty((w.E, K // g, N), dtype=np.uint16)
+            canon = (torch.empty((1, K, N), dtype=torch.int8, device=device) if w.bits == 8
+                     else torch.empty((1, K, N // 2), dtype=torch.uint8, device=device))
+            for e0, masters in W.expert_weight_batches(w, which, batch=batch):
+                oq, os_ = oracle.quantize(np.stack(masters), w.bits, w.group_size)
+                for i, m in enumerate(masters):
+                    e = e0 + i
+                    self.layer.load_expert(which, e, to_dev(m, torch.float32, device), canon)
+                    got_q = canon.cpu().numpy()[0]
+                    got_s = (self.layer.s1 if which == 1 else self.layer.s2)[e].cpu().numpy().view(np.uint16)
+                    want_q = oq[i] if w.bits == 8 else oracle.pack_int4(oq[i])
+                    self.quant_mismatches += int((got_q != want_q).sum()) + int((got_s != os_[i]).sum())
+                    if keep_oracle_weights:
+                        self.q[which][e] = oq[i]
+                        self.s[which][e] = os_[i]
+        torch.cuda.synchronize()
+
+    def oracle_routing(self):
+        w = self.w
+        idx, scale = oracle.gate(self.x, self.wg, self.bias, w.k, w.renormalize)
+        perm_src, inv_perm, off = oracle.permute(idx, w.E)
+        return idx, scale, perm_src, inv_perm, off
+
+    def oracle_out_for_tokens(self, tokens, idx, scale, perm_src, inv_perm, off, y_dtype):
+        """Oracle output rows for the chosen tokens only (exact: rows are independent)."""
+        w = self.w
+        tokens = np.asarray(sorted(tokens), dtype=np.int64)
+        rows = np.sort(np.concatenate([inv_perm[tokens * w.k + j] for j in range(w.k)]))
+        x_perm = oracle.gather_rows(self.x, perm_src, w.k)
+        y = oracle.grouped_ffn(x_perm, off, self.q[1], self.s[1], self.q[2], self.s[2], w.group_size,
+                               ORC_DT[w.act], rows=rows)
+        y = oracle.round_to(y, y_dtype)
+        out = oracle.combine(y, inv_perm, scale, w.T, w.k)
+        return tokens, out[tokens]
+
+
+def error_metrics(got: np.ndarray, want: np.ndarray):
+    got = got.astype(np.float64)
+    want = want.astype(np.float64)
+    max_abs = float(np.abs(got - want).max()) if got.size else 0.0
+    denom = float(np.sqrt((want ** 2).sum()))
+    rel_l2 = float(np.sqrt(((got - want) ** 2).sum()) / denom) if denom > 0 else 0.0
+    return max_abs, rel_l2
+
+
+def oracle_dtype_code(torch_dtype):
+    return {torch.float16: oracle.F16, torch.bfloat16: oracle.BF16, torch.float32: oracle.F32}[torch_dtype]

@@ -1,0 +1,67 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2211_10017_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2211_10017_amd.build import build_library
+        build_library()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "moe_wq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.moe_abi_version() == 1
+
+
+def test_workspace_queries_are_host_functions(lib):
+    assert lib.moe_permute_workspace_bytes(64, 2, 32) >= 16
+    small = lib.moe_grouped_ffn_wq_workspace_bytes(128, 1024, 4096, 32, binding.MOE_F16)
+    assert small >= 128 * 4096 * 2
+    assert lib.moe_grouped_ffn_wq_workspace_bytes(128, 1024, 4096, 32, binding.MOE_BF16) > small
+    assert lib.moe_permute_workspace_bytes(16384, 1, 64) >= 16 * 4 * 64 * 4
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)          # never dereferenced: validation fails first
+    assert lib.moe_quantize_experts(None, 1, 64, 32, 4, 0, None, None, None, None) == 1
+    assert b"NULL" in lib.moe_last_error()
+    assert lib.moe_quantize_experts(fake, 1, 64, 32, 3, 0, fake, fake, fake, None) == 2
+    assert lib.moe_quantize_experts(fake, 1, 60, 32, 4, 0, fake, fake, fake, None) == 1
+    assert lib.moe_quantize_experts(fake, 1, 128, 32, 4, 48, fake, fake, fake, None) == 1
+    assert lib.moe_gate_topk(fake, 0, fake, None, 4, 64, 8, 3, 1, fake, fake, None) == 1      # k = 3
+    assert lib.moe_gate_topk(fake, 0, fake, None, 4, 64, 1, 2, 1, fake, fake, None) == 1      # k > E
+    assert lib.moe_gate_topk(fake, 2, fake, None, 4, 64, 8, 1, 1, fake, fake, None) == 2      # fp32 x
+    assert lib.moe_gate_topk(fake, 0, fake, None, 4, 64, 300, 1, 1, fake, fake, None) == 2    # E too large
+    assert lib.moe_permute(fake, fake, 0, 4, 1, 8, 60, fake, fake, fake, fake, None, 0, None) == 1   # row not 16 B
+    assert lib.moe_permute(fake, fake, 0, 8192, 1, 8, 64, fake, fake, fake, fake, None, 0, None) == 3  # no workspace
+    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 96, 128, 4, 0, fake, fake, None, fake, fake, None,
+                                  fake, 0, fake, 1 << 20, None) == 1                           # d % 64
+    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 64, 128, 4, 0, fake, fake, None, fake, fake, None,
+                                  fake, 0, fake, 16, None) == 3                                # workspace too small
+    assert b"workspace" in lib.moe_last_error()
+    assert lib.moe_combine(fake, 0, fake, fake, 4, 1, 60, fake, 2, None) == 1
+    assert lib.moe_combine(fake, 5, fake, fake, 4, 1, 64, fake, 2, None) == 2
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(binding.MoeError):
+        binding.load()
