@@ -75,11 +75,11 @@ extern "C" int moe_combine(const void *y_perm, int y_dtype, const int32_t *inv_p
                            void *stream)
 {
     using namespace moe;
+    if (T == 0 && k > 0 && d > 0) return MOE_OK;         // empty buffers may be NULL
     if (!y_perm || !inv_perm || !expert_scale || !out) return fail(MOE_ERR_INVALID_ARG, "moe_combine: NULL pointer");
     if (T < 0 || k <= 0 || d <= 0 || d % 8) return fail(MOE_ERR_INVALID_ARG, "moe_combine: need T >= 0, k > 0, d > 0, d %% 8 == 0");
     if (y_dtype < 0 || y_dtype > 2 || out_dtype < 0 || out_dtype > 2) return fail(MOE_ERR_UNSUPPORTED, "moe_combine: unknown dtype");
     if (!aligned16(y_perm) || !aligned16(out)) return fail(MOE_ERR_INVALID_ARG, "moe_combine: buffers must be 16-byte aligned");
-    if (T == 0) return MOE_OK;
     const int d4 = d / 4;
     size_t blocks = ((size_t)T * d4 + 255) / 256;
     if (blocks > 16384) blocks = 16384;

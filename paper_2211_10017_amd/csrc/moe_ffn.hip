@@ -396,7 +396,7 @@ extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32
                                   size_t workspace_bytes, void *stream)
 {
     using namespace moe;
-    if (!x_perm || !expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || !y_perm)
+    if (!expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || (R != 0 && (!x_perm || !y_perm)))
         return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: NULL pointer");
     if (R < 0 || E <= 0 || d <= 0 || F <= 0) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: R >= 0 and E, d, F > 0 required");
     if (d % 64 || F % 64) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: d and F must be multiples of 64 (d=%d F=%d)", d, F);

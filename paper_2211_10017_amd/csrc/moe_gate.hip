@@ -159,6 +159,7 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
                              float *expert_scale, void *stream)
 {
     using namespace moe;
+    if (T == 0 && d > 0 && E > 0) return MOE_OK;         // nothing to route (empty buffers may be NULL)
     if (!x || !wg || !expert_idx || !expert_scale) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: NULL pointer");
     if (T < 0 || d <= 0 || E <= 0) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: T >= 0, d > 0, E > 0 required");
     if (d % 8) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: d %% 8 != 0 (d=%d)", d);
@@ -166,7 +167,6 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     if (E > 256) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: E=%d above 256", E);
     if (act_dtype != MOE_F16 && act_dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: act_dtype must be fp16 or bf16");
     if (!aligned16(x)) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: x must be 16-byte aligned");
-    if (T == 0) return MOE_OK;
     int EL = 8;
     while (EL < E && EL < 64) EL *= 2;
     const int NE = (E + 63) / 64;

@@ -163,8 +163,9 @@ extern "C" int moe_permute(const int32_t *expert_idx, const void *x, int act_dty
                            void *stream)
 {
     using namespace moe;
-    if (!expert_idx || !perm_src || !inv_perm || !expert_offsets) return fail(MOE_ERR_INVALID_ARG, "moe_permute: NULL index pointer");
-    if ((x == nullptr) != (x_perm == nullptr)) return fail(MOE_ERR_INVALID_ARG, "moe_permute: x and x_perm must both be given or both be NULL");
+    if (!expert_offsets || (T > 0 && (!expert_idx || !perm_src || !inv_perm)))
+        return fail(MOE_ERR_INVALID_ARG, "moe_permute: NULL index pointer");
+    if (T > 0 && (x == nullptr) != (x_perm == nullptr)) return fail(MOE_ERR_INVALID_ARG, "moe_permute: x and x_perm must both be given or both be NULL");
     if (T < 0 || k <= 0 || E <= 0 || d <= 0) return fail(MOE_ERR_INVALID_ARG, "moe_permute: T >= 0 and k, E, d > 0 required");
     if (E > kPermMaxE) return fail(MOE_ERR_UNSUPPORTED, "moe_permute: E=%d above %d", E, kPermMaxE);
     if (act_dtype != MOE_F16 && act_dtype != MOE_BF16 && act_dtype != MOE_F32) return fail(MOE_ERR_UNSUPPORTED, "moe_permute: unknown act_dtype %d", act_dtype);

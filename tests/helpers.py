@@ -47,6 +47,8 @@ class Prepared:
             canon = (torch.empty((1, K, N), dtype=torch.int8, device=device) if w.bits == 8
                      else torch.empty((1, K, N // 2), dtype=torch.uint8, device=device))
             for e0, masters in W.expert_weight_batches(w, which, batch=batch):
+                if e0 % (4 * batch) == 0:
+                    print(f"   {w.name}: quantising W{which} experts {e0}.. of {w.E}", flush=True)
                 oq, os_ = oracle.quantize(np.stack(masters), w.bits, w.group_size)
                 for i, m in enumerate(masters):
                     e = e0 + i

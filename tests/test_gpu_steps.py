@@ -98,6 +98,15 @@ def test_permute_bit_exact(T, k, E, d):
     assert np.array_equal(xp.cpu().numpy(), x[perm_src // k])
 
 
+def test_permute_no_tokens():
+    _say("permute T=0")
+    idx = torch.empty((0, 2), dtype=torch.int32, device=DEV)
+    x = torch.empty((0, 64), dtype=torch.float16, device=DEV)
+    xp, ps, ip, of = B.moe_permute(idx, x, 5)
+    torch.cuda.synchronize()
+    assert xp.shape == (0, 64) and not of.cpu().numpy().any() and of.numel() == 6
+
+
 # ------------------------------------------------------------------ grouped FFN
 def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False):
     rng = np.random.default_rng(seed)
