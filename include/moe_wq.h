@@ -117,6 +117,10 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  * registers (never written back to memory).  Experts without rows cost no weight traffic.
  *
  *   x_perm [R,d] act_dtype; expert_offsets [E+1]
+ *   max_rows_per_expert: an upper bound on the rows any one expert receives, if the caller
+ *       knows one (T is one: a token visits an expert at most once); 0 = unknown.  It only
+ *       steers the choice between the weight-streaming and the tiled kernel: results do not
+ *       depend on it, also when it is wrong.
  *   w1_packed / w2_packed: q_packed from moe_quantize_experts for (E,d,F) / (E,F,d)
  *   s1 fp16 [E, d/g, F]; s2 fp16 [E, F/g, d]  (g = group_size, or K when group_size is 0)
  *   b1 [E,F] / b2 [E,d] fp16 or NULL
@@ -126,7 +130,8 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  */
 size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E, int act_dtype);
 int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
-                       int E, int d, int F, int bits, int group_size, const void *w1_packed,
+                       int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                       const void *w1_packed,
                        const void *s1, const void *b1, const void *w2_packed, const void *s2,
                        const void *b2, void *y_perm, int y_dtype, void *workspace,
                        size_t workspace_bytes, void *stream);

@@ -53,7 +53,7 @@ def load():
     lib.moe_grouped_ffn_wq_workspace_bytes.restype = sz
     lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_ffn_wq.restype = i
-    lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.moe_combine.restype = i
     lib.moe_combine.argtypes = [vp, i, vp, vp, i, i, i, vp, i, vp]
     _lib = lib
@@ -154,7 +154,7 @@ def moe_grouped_ffn_wq_workspace_bytes(R: int, d: int, F: int, E: int, act_dtype
 
 def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
                        w1_packed, s1, w2_packed, s2, b1=None, b2=None, y_dtype=None, y_perm=None,
-                       workspace=None):
+                       workspace=None, max_rows_per_expert: int = 0):
     R = x_perm.shape[0]
     y_dtype = y_dtype or x_perm.dtype
     if y_perm is None:
@@ -164,7 +164,7 @@ def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int
                                 dtype=torch.uint8, device=x_perm.device)
     rc = load().moe_grouped_ffn_wq(
         _ptr(x_perm, (torch.float16, torch.bfloat16), "x_perm"), _DT[x_perm.dtype],
-        _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E, d, F, bits, group_size,
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E, max_rows_per_expert, d, F, bits, group_size,
         _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"), _ptr(b1, torch.float16, "b1"),
         _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"), _ptr(b2, torch.float16, "b2"),
         _ptr(y_perm), _DT[y_perm.dtype], _ptr(workspace), workspace.numel(), _stream())

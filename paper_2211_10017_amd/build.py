@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmoe_wq.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["moe_errors.hip", "moe_quantize.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip",
+SOURCES = ["moe_errors.hip", "moe_quantize.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip", "moe_ffn_tiled.hip", "moe_ffn_stream.hip",
            "moe_combine.hip"]
 
 # packed-fp32 VALU forms are switched off for every translation unit of this library
@@ -40,7 +40,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_library(jobs: int = 6) -> str:
+def build_library(jobs: int = 8) -> str:
     """Compile every source and link the shared library; always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:

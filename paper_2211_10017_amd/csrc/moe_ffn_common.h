@@ -1,0 +1,129 @@
+// Device helpers shared by the grouped-GEMM kernels: argument block, the magic-number
+// integer-to-FP16 conversions (Sec. 3.4.1-3.4.3) and the tile lookup.
+#pragma once
+
+#include "moe_common.h"
+
+namespace moe {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+enum { SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_GROUP_SPLIT = 2 };
+
+struct GemmArgs {
+    const uint16_t *a;        // [R, K] fp16 or bf16 bit patterns
+    const float2 *row_pow;    // bf16 only: per row (2^-p, 2^p) normalisation factors
+    const int32_t *offsets;   // [E+1]
+    const uint8_t *wq;        // packed codes, [E] x packed_bytes_per_expert
+    const __half *scales;     // [E, K/g, N]
+    const __half *bias;       // [E, N] or null
+    void *out;                // [R, N]
+    int E, R, K, N, g;
+    int out_dtype, relu;
+    int row_lo;               // tiled kernel: only experts with more than row_lo rows
+    int row_hi;               // streaming kernel: only experts with 1..row_hi rows
+};
+
+int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);
+int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hipStream_t s);
+bool stream_gemm_supports(int K, int bits, int smode);
+int stream_gemm_fit_rows(int K);
+
+__device__ inline uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
+
+// Sec. 3.4.1: OR-ing an unsigned code Y < 1024 into the mantissa of FP16 1024.0 (0x6400) gives
+// the FP16 number 1024 + Y; an FP16 subtraction of 1024 + offset returns the signed integer,
+// exactly.  Two codes are converted per 32-bit register.
+//
+// 4-bit (Sec. 3.4.3): the eight codes of a dword sit in nibble positions 0,4,1,5,2,6,3,7, so
+// (x & 0x000f000f) | 0x64006400 is the pair (i0, i1) + 1024 and (x & 0x00f000f0) | 0x64006400 is
+// 16 * (i2, i3) + 1024; the latter is brought back with one fma: v/16 - (64 + 8).
+__device__ inline void dequant4(uint32_t x, uint32_t out[4])
+{
+    const uint32_t magic = 0x64006400u;
+    const half2_t sub = {(_Float16)1032.0f, (_Float16)1032.0f};
+    const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const half2_t sub16 = {(_Float16)72.0f, (_Float16)72.0f};
+    const uint32_t lo0 = (x & 0x000f000fu) | magic;
+    const uint32_t hi0 = (x & 0x00f000f0u) | magic;
+    x >>= 8;
+    const uint32_t lo1 = (x & 0x000f000fu) | magic;
+    const uint32_t hi1 = (x & 0x00f000f0u) | magic;
+    out[0] = h2_bits(bits_h2(lo0) - sub);
+    out[1] = h2_bits(bits_h2(hi0) * sixteenth - sub16);
+    out[2] = h2_bits(bits_h2(lo1) - sub);
+    out[3] = h2_bits(bits_h2(hi1) * sixteenth - sub16);
+}
+
+// 8-bit (Sec. 3.4.2): four codes (+128) per dword; a byte permute builds 0x64xx64yy for two of
+// them at a time, and an FP16 subtraction of 1152 = 1024 + 128 returns the signed integers.
+__device__ inline void dequant8(uint32_t w0, uint32_t w1, uint32_t out[4])
+{
+    const half2_t sub = {(_Float16)1152.0f, (_Float16)1152.0f};
+    const uint32_t magic = 0x64646464u;
+    out[0] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w0, 0x04010400u)) - sub);
+    out[1] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w0, 0x04030402u)) - sub);
+    out[2] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w1, 0x04010400u)) - sub);
+    out[3] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w1, 0x04030402u)) - sub);
+}
+
+__device__ inline half8_t frag_from(const uint32_t w[4])
+{
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    u4 v = {w[0], w[1], w[2], w[3]};
+    return __builtin_bit_cast(half8_t, v);
+}
+
+__device__ inline uint16_t to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ inline void store_out(void *out, int dtype, size_t o, float v)
+{
+    if (dtype == MOE_F32) reinterpret_cast<float *>(out)[o] = v;
+    else if (dtype == MOE_BF16) reinterpret_cast<uint16_t *>(out)[o] = to_bf16_rne(v);
+    else reinterpret_cast<_Float16 *>(out)[o] = (_Float16)v;
+}
+
+// Finds the (expert, row tile) of tile slot `slot`: experts are walked 64 at a time, each lane
+// holding one expert's tile count, with a shuffle scan.  Every wavefront computes the same
+// answer; returns false when the slot is past the last tile.
+__device__ inline bool find_tile(const int32_t *offsets, int E, int BM, int row_lo, int slot,
+                                 int *e_out, int *row0, int *rows)
+{
+    const int lane = threadIdx.x & 63;
+    int base = 0;
+    for (int e0 = 0; e0 < E; e0 += 64) {
+        const int e = e0 + lane;
+        int lo = 0, hi = 0;
+        if (e < E) { lo = offsets[e]; hi = offsets[e + 1]; }
+        const int tiles = hi - lo > row_lo ? (hi - lo + BM - 1) / BM : 0;
+        int incl = tiles;
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const uint64_t hit = __ballot(base + incl > slot);
+        if (hit) {
+            const int src = __ffsll((unsigned long long)hit) - 1;
+            const int excl = __shfl(incl - tiles, src);
+            const int mt = slot - base - excl;
+            const int lo_s = __shfl(lo, src), hi_s = __shfl(hi, src);
+            *e_out = e0 + src;
+            *row0 = lo_s + mt * BM;
+            *rows = min(BM, hi_s - (lo_s + mt * BM));
+            return true;
+        }
+        base += __shfl(incl, 63);
+    }
+    return false;
+}
+
+}  // namespace moe

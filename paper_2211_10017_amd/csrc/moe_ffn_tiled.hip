@@ -1,0 +1,227 @@
+// LDS-tiled grouped GEMM with fused dequantisation, for experts with many rows
+// (Sec. 3.3 grouped GEMM, Sec. 3.4 fused dequantisation).
+//
+// Tokens are the MFMA A operand (rows), weights the B operand (columns).  A wavefront fetches
+// its weight fragments straight from HBM into registers (one 16-byte load per lane per 1 KB
+// fragment block, see moe_common.h), converts the codes to FP16 with the 0x6400 trick and
+// feeds v_mfma_f32_32x32x16_f16; only the activations go through LDS, shared by the four
+// wavefronts of a block, each of which owns its own 64 output channels.
+#include "moe_ffn_common.h"
+
+namespace moe {
+
+constexpr int kLdsRow = 64 + 8;          // halfs per LDS row: 144-byte stride, conflict-free b128 reads
+constexpr int kTN = 2;                   // 32-channel tiles per wavefront
+
+template <int BITS, int SMODE, bool ABF16, int TM>
+__global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs p)
+{
+    constexpr int BM = 32 * TM;
+    constexpr int NW = BITS == 4 ? 1 : 2;             // 16-byte loads per tile per 64-deep K step
+    __shared__ __align__(16) uint16_t lds_a[2][BM * kLdsRow];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int e, row0, rows;
+    if (!find_tile(p.offsets, p.E, BM, p.row_lo, blockIdx.y, &e, &row0, &rows)) return;
+
+    const int K = p.K, N = p.N;
+    const int nk = K / 64;
+    const int ntile0 = (blockIdx.x * 4 + wave) * kTN;  // first 32-channel tile of this wavefront
+    const int ntiles = N / 32;
+    bool tile_ok[kTN];
+#pragma unroll
+    for (int t = 0; t < kTN; ++t) tile_ok[t] = ntile0 + t < ntiles;
+
+    // ---- global addresses
+    // A: thread loads 16 bytes = 8 K values of row (tid/8 + 32*pass)
+    const int a_row = threadIdx.x >> 3, a_seg = (threadIdx.x & 7) * 8;
+    const uint16_t *a_ptr[TM];
+    float a_down[TM];
+#pragma unroll
+    for (int m = 0; m < TM; ++m) {
+        const int r = row0 + min(a_row + 32 * m, rows - 1);      // clamped: always a valid row
+        a_ptr[m] = p.a + (size_t)r * K + a_seg;
+        a_down[m] = ABF16 ? p.row_pow[r].x : 1.0f;
+    }
+    // B: fragment blocks of tile t are contiguous along K
+    const uint8_t *w_e = p.wq + (size_t)e * packed_bytes_per_expert(K, N, BITS);
+    const uint4 *b_ptr[kTN];
+#pragma unroll
+    for (int t = 0; t < kTN; ++t) {
+        const int nt = tile_ok[t] ? ntile0 + t : 0;
+        b_ptr[t] = reinterpret_cast<const uint4 *>(w_e + (size_t)nt * (K / frag_k(BITS)) * kFragBytes) + lane;
+    }
+    const int G = K / p.g;
+    const __half *s_ptr[kTN];
+#pragma unroll
+    for (int t = 0; t < kTN; ++t) {
+        const int nt = tile_ok[t] ? ntile0 + t : 0;
+        s_ptr[t] = p.scales + (size_t)e * G * N + nt * 32 + (lane & 31);
+    }
+
+    float16_t acc[TM][kTN];
+#pragma unroll
+    for (int m = 0; m < TM; ++m)
+#pragma unroll
+        for (int t = 0; t < kTN; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.0f;
+
+    uint4 ga[TM], gb[kTN][NW];
+    _Float16 gs[kTN];
+    auto load_global = [&](int kb) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kb * 64);
+#pragma unroll
+        for (int t = 0; t < kTN; ++t) {
+#pragma unroll
+            for (int w = 0; w < NW; ++w) gb[t][w] = b_ptr[t][(size_t)(kb * NW + w) * 64];
+            if (SMODE != SCALE_CHANNEL) gs[t] = __builtin_bit_cast(_Float16, s_ptr[t][(size_t)((kb * 64) / p.g) * N]);
+        }
+    };
+
+    load_global(0);
+    for (int kb = 0; kb < nk; ++kb) {
+        uint16_t *stage = lds_a[kb & 1];
+        // ---- activations to LDS (bf16 rows are scaled by a power of two into FP16 range)
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            uint4 v = ga[m];
+            if (ABF16) {
+                uint32_t in[4] = {v.x, v.y, v.z, v.w}, o[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float f0 = __uint_as_float(in[q] << 16) * a_down[m];
+                    const float f1 = __uint_as_float(in[q] & 0xffff0000u) * a_down[m];
+                    const half2_t h = {(_Float16)f0, (_Float16)f1};
+                    o[q] = h2_bits(h);
+                }
+                v = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
+        }
+        // ---- this step's weight fragments: unpack + convert in registers
+        uint32_t bw[kTN][4][4], bl[kTN][4][4];
+#pragma unroll
+        for (int t = 0; t < kTN; ++t) {
+            uint32_t raw[NW * 4];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                raw[4 * w + 0] = gb[t][w].x; raw[4 * w + 1] = gb[t][w].y;
+                raw[4 * w + 2] = gb[t][w].z; raw[4 * w + 3] = gb[t][w].w;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (BITS == 4) dequant4(raw[j], bw[t][j]);
+                else dequant8(raw[2 * j], raw[2 * j + 1], bw[t][j]);
+                if (SMODE == SCALE_GROUP) {
+                    const half2_t s2 = {gs[t], gs[t]};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) bw[t][j][q] = h2_bits(bits_h2(bw[t][j][q]) * s2);
+                } else if (SMODE == SCALE_GROUP_SPLIT) {
+                    // exact two-term weight: hi = fl(q*s'), lo = q*s' - hi, with s' = 256*s so
+                    // that lo stays a normal FP16 number; the epilogue divides by 256
+                    const _Float16 s8 = gs[t] * (_Float16)256.0f;
+                    const half2_t s2 = {s8, s8};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const half2_t qv = bits_h2(bw[t][j][q]);
+                        const half2_t hi = qv * s2;
+                        half2_t lo;
+                        lo[0] = __builtin_fmaf16(qv[0], s2[0], -hi[0]);
+                        lo[1] = __builtin_fmaf16(qv[1], s2[1], -hi[1]);
+                        bw[t][j][q] = h2_bits(hi);
+                        bl[t][j][q] = h2_bits(lo);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (kb + 1 < nk) load_global(kb + 1);
+        // ---- MFMA over the four 16-deep steps of this K slab
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                const half8_t af = *reinterpret_cast<const half8_t *>(
+                    stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
+#pragma unroll
+                for (int t = 0; t < kTN; ++t) {
+                    acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[t][j]), acc[m][t], 0, 0, 0);
+                    if (SMODE == SCALE_GROUP_SPLIT)
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[t][j]), acc[m][t], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: scale (per channel), bias, ReLU, store.  acc[m][t][i] is row
+    // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
+#pragma unroll
+    for (int t = 0; t < kTN; ++t) {
+        if (!tile_ok[t]) continue;
+        const int n = (ntile0 + t) * 32 + (lane & 31);
+        float cs = 1.0f;
+        if (SMODE == SCALE_CHANNEL) cs = __half2float(p.scales[(size_t)e * N + n]);
+        if (SMODE == SCALE_GROUP_SPLIT) cs = 1.0f / 256.0f;
+        const float bias = p.bias ? __half2float(p.bias[(size_t)e * N + n]) : 0.0f;
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                if (rl >= rows) continue;
+                const int r = row0 + rl;
+                float v = acc[m][t][i] * cs;
+                if (ABF16) v *= p.row_pow[r].y;
+                v += bias;
+                if (p.relu) v = fmaxf(v, 0.0f);
+                const size_t o = (size_t)r * N + n;
+                if (p.out_dtype == MOE_F32) reinterpret_cast<float *>(p.out)[o] = v;
+                else if (p.out_dtype == MOE_BF16) reinterpret_cast<uint16_t *>(p.out)[o] = to_bf16_rne(v);
+                else reinterpret_cast<_Float16 *>(p.out)[o] = (_Float16)v;
+            }
+        }
+    }
+}
+
+template <int BITS, int SMODE, bool ABF16>
+static void launch_tm(const GemmArgs &p, int tm, dim3 grid, hipStream_t s)
+{
+    if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 1>), grid, dim3(256), 0, s, p);
+    else if (tm == 2) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 2>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 4>), grid, dim3(256), 0, s, p);
+}
+
+template <int BITS>
+static void launch_mode(const GemmArgs &p, int smode, bool abf16, int tm, dim3 grid, hipStream_t s)
+{
+    if (smode == SCALE_CHANNEL) {
+        if (abf16) launch_tm<BITS, SCALE_CHANNEL, true>(p, tm, grid, s);
+        else launch_tm<BITS, SCALE_CHANNEL, false>(p, tm, grid, s);
+    } else if (smode == SCALE_GROUP) {
+        if (abf16) launch_tm<BITS, SCALE_GROUP, true>(p, tm, grid, s);
+        else launch_tm<BITS, SCALE_GROUP, false>(p, tm, grid, s);
+    } else {
+        if (abf16) launch_tm<BITS, SCALE_GROUP_SPLIT, true>(p, tm, grid, s);
+        else launch_tm<BITS, SCALE_GROUP_SPLIT, false>(p, tm, grid, s);
+    }
+}
+
+int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s)
+{
+    // row-tile height from the mean rows per expert (the offsets themselves stay on the device)
+    const int mean = (p.R + p.E - 1) / p.E;
+    const int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
+    const int bm = 32 * tm;
+    const long most = (long)p.R / (p.row_lo + 1);               // experts that can exceed row_lo rows
+    const long slots = (long)p.R / bm + (p.E < most ? p.E : most);
+    if (slots == 0) return MOE_OK;
+    if (slots > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: %ld row tiles exceed one launch", slots);
+    dim3 grid((p.N + 255) / 256, (unsigned)slots);
+    if (bits == 4) launch_mode<4>(p, smode, abf16, tm, grid, s);
+    else launch_mode<8>(p, smode, abf16, tm, grid, s);
+    return check_launch("moe_grouped_ffn_wq (gemm)");
+}
+
+}  // namespace moe

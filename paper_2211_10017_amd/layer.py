@@ -66,7 +66,8 @@ class MoEExpertLayer:
     def ffn(self):
         return B.moe_grouped_ffn_wq(self.x_perm, self.expert_offsets, self.E, self.d, self.F, self.bits,
                                     self.group_size, self.w1_packed, self.s1, self.w2_packed, self.s2,
-                                    self.b1, self.b2, y_perm=self.y_perm, workspace=self.ws_ffn)
+                                    self.b1, self.b2, y_perm=self.y_perm, workspace=self.ws_ffn,
+                                    max_rows_per_expert=self.T)
 
     def combine(self):
         return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out)

@@ -137,6 +137,10 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False):
 @pytest.mark.parametrize("rows,d,F,bits,g,act,y_dt", [
     ([5, 0, 33, 1, 70], 128, 256, 4, 0, "f16", torch.float16),
     ([40], 1024, 4096, 4, 0, "f16", torch.float16),
+    ([4], 1024, 4096, 4, 0, "f16", torch.float16),
+    ([8, 9], 1024, 2048, 4, 0, "f16", torch.float32),
+    ([32, 33, 1], 1024, 1024, 4, 0, "f16", torch.float32),
+    ([7, 0, 16], 512, 2048, 8, 0, "f16", torch.float16),
     ([3, 4, 0, 0, 9, 2, 1, 6], 1024, 4096, 4, 0, "f16", torch.float32),
     ([31, 32, 33, 64, 65, 0, 129], 192, 320, 8, 0, "f16", torch.float16),
     ([100, 260, 7], 256, 512, 4, 128, "f16", torch.float16),
