@@ -41,17 +41,27 @@ __device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_
 // 4-bit (Sec. 3.4.3): the eight codes of a dword sit in nibble positions 0,4,1,5,2,6,3,7, so
 // (x & 0x000f000f) | 0x64006400 is the pair (i0, i1) + 1024 and (x & 0x00f000f0) | 0x64006400 is
 // 16 * (i2, i3) + 1024; the latter is brought back with one fma: v/16 - (64 + 8).
+// (x & mask) | magic in one VALU instruction.  The compiler prefers two VOP2 instructions with
+// literal operands here (VOP3 cannot encode literals on this target), so the instruction is
+// spelled out, with mask and magic held in registers.
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(mask), "v"(magic));
+    return r;
+}
+
 __device__ inline void dequant4(uint32_t x, uint32_t out[4])
 {
-    const uint32_t magic = 0x64006400u;
+    const uint32_t magic = 0x64006400u, mlo = 0x000f000fu, mhi = 0x00f000f0u;
     const half2_t sub = {(_Float16)1032.0f, (_Float16)1032.0f};
     const half2_t sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
     const half2_t sub16 = {(_Float16)72.0f, (_Float16)72.0f};
-    const uint32_t lo0 = (x & 0x000f000fu) | magic;
-    const uint32_t hi0 = (x & 0x00f000f0u) | magic;
+    const uint32_t lo0 = and_or(x, mlo, magic);
+    const uint32_t hi0 = and_or(x, mhi, magic);
     x >>= 8;
-    const uint32_t lo1 = (x & 0x000f000fu) | magic;
-    const uint32_t hi1 = (x & 0x00f000f0u) | magic;
+    const uint32_t lo1 = and_or(x, mlo, magic);
+    const uint32_t hi1 = and_or(x, mhi, magic);
     out[0] = h2_bits(bits_h2(lo0) - sub);
     out[1] = h2_bits(bits_h2(hi0) * sixteenth - sub16);
     out[2] = h2_bits(bits_h2(lo1) - sub);

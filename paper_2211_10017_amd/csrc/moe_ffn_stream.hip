@@ -17,7 +17,10 @@
 namespace moe {
 
 constexpr int kRing = 16;             // weight fragment blocks in flight per wavefront
-constexpr int kStreamLds = 72 * 1024;  // LDS per block for an expert's activation rows (2 blocks per CU)
+#ifndef MOE_STREAM_LDS_KB
+#define MOE_STREAM_LDS_KB 72
+#endif
+constexpr int kStreamLds = MOE_STREAM_LDS_KB * 1024;  // LDS per block for an expert's activation rows (2 blocks per CU)
 constexpr int kRowPad = 8;             // halfs of padding per LDS row: rows start 4 banks apart
 
 // Rows of one expert that fit in LDS together, for the whole K range (at most one 32-row tile).

@@ -1,6 +1,7 @@
 // moe_gate_topk: router logits, top-k selection and gate probabilities (Sec. 3.3).
 //
-// Mapping: a lane owns one expert (NE experts when E > 64) for TB tokens; when E < 64 a
+// Mapping: a lane owns one expert (NE experts when E > 64) for TB tokens (TB = 1 when there are
+// few tokens, so that they spread over more blocks); when E < 64 a
 // wavefront is cut into 64/EL token groups of EL = pow2ceil(E) lanes.  The four wavefronts of
 // a block take the four partial sums of the contract (128-element blocks of the feature axis
 // dealt round-robin), so the floating-point order is fixed by the definition, not by the
@@ -11,7 +12,6 @@
 
 namespace moe {
 
-constexpr int kGateTB = 4;       // tokens per lane group
 constexpr int kGateBlk = 128;    // feature block of one partial-sum turn
 
 template <bool BF16>
@@ -23,7 +23,9 @@ __device__ inline float act_to_float(uint16_t v)
     return __half2float(h);
 }
 
-template <bool BF16, int NE>
+// With E <= 64 the 128 x E block of the gate weight that a wavefront needs per turn is copied
+// to LDS with 16-byte loads first (one latency per turn instead of one per row).
+template <bool BF16, int NE, int TB>
 __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ x,
                                                    const uint16_t *__restrict__ wg,
                                                    const float *__restrict__ bias, int T, int d,
@@ -35,18 +37,21 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int G = 64 / EL;                        // token groups per wavefront
     const int grp = lane / EL, le = lane % EL;
-    const int ntok = G * kGateTB;                 // tokens per block
+    const int ntok = G * TB;                 // tokens per block
     const int t0 = blockIdx.x * ntok;
 
-    // wave-private staging area for x: [ntok][128] 16-bit values
-    uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * ntok * kGateBlk;
-    float *part = reinterpret_cast<float *>(smem + (size_t)4 * ntok * kGateBlk * 2);  // [4][NE][TB][64]
+    // wave-private staging areas: x [ntok][128] and (NE == 1) the gate weight block [128][E]
+    constexpr bool WLDS = NE == 1;
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateBlk * E : 0);
+    uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * wave_halfs;
+    uint16_t *ws = xs + (size_t)ntok * kGateBlk;
+    float *part = reinterpret_cast<float *>(smem + (size_t)4 * wave_halfs * 2);  // [4][NE][TB][64]
 
-    float acc[NE][kGateTB];
+    float acc[NE][TB];
 #pragma unroll
     for (int a = 0; a < NE; ++a)
 #pragma unroll
-        for (int b = 0; b < kGateTB; ++b) acc[a][b] = 0.0f;
+        for (int b = 0; b < TB; ++b) acc[a][b] = 0.0f;
 
     const int nblk = (d + kGateBlk - 1) / kGateBlk;
     const int turns = (nblk + 3) / 4;             // same trip count for all four wavefronts
@@ -62,6 +67,19 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             if (seg < lim) v = *reinterpret_cast<const uint4 *>(x + (size_t)t * d + i0 + seg);
             *reinterpret_cast<uint4 *>(xs + row * kGateBlk + seg) = v;
         }
+        if (WLDS) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(wg + (size_t)i0 * E);
+            const int nvec = lim * E / 8;
+            for (int v0 = 0; v0 < nvec; v0 += 64 * 8) {          // eight loads in flight per lane
+                uint4 tmp[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (v0 + u * 64 + lane < nvec) tmp[u] = src[v0 + u * 64 + lane];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (v0 + u * 64 + lane < nvec) reinterpret_cast<uint4 *>(ws)[v0 + u * 64 + lane] = tmp[u];
+            }
+        }
         __syncthreads();
         for (int i = 0; i < lim; i += 8) {
             float wv[NE][8];
@@ -69,11 +87,12 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             for (int a = 0; a < NE; ++a) {
                 const int e = min(a * 64 + le, E - 1);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>(wg[(size_t)(i0 + i + u) * E + e]);
+                for (int u = 0; u < 8; ++u)
+                    wv[a][u] = act_to_float<BF16>(WLDS ? ws[(i + u) * E + e] : wg[(size_t)(i0 + i + u) * E + e]);
             }
 #pragma unroll
-            for (int b = 0; b < kGateTB; ++b) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(xs + (grp * kGateTB + b) * kGateBlk + i);
+            for (int b = 0; b < TB; ++b) {
+                const uint4 raw = *reinterpret_cast<const uint4 *>(xs + (grp * TB + b) * kGateBlk + i);
                 const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
@@ -89,21 +108,22 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 #pragma unroll
     for (int a = 0; a < NE; ++a)
 #pragma unroll
-        for (int b = 0; b < kGateTB; ++b) part[((wave * NE + a) * kGateTB + b) * 64 + lane] = acc[a][b];
+        for (int b = 0; b < TB; ++b) part[((wave * NE + a) * TB + b) * 64 + lane] = acc[a][b];
     __syncthreads();
 
     // wavefront `wave` finishes token slot b = wave of every group
+    if (wave >= TB) return;
     const int b = wave;
-    const int t = t0 + grp * kGateTB + b;
+    const int t = t0 + grp * TB + b;
     float lg[NE];
     const float NEG = -INFINITY;
 #pragma unroll
     for (int a = 0; a < NE; ++a) {
         const int e = a * 64 + le;
-        float p0 = part[((0 * NE + a) * kGateTB + b) * 64 + lane];
-        float p1 = part[((1 * NE + a) * kGateTB + b) * 64 + lane];
-        float p2 = part[((2 * NE + a) * kGateTB + b) * 64 + lane];
-        float p3 = part[((3 * NE + a) * kGateTB + b) * 64 + lane];
+        float p0 = part[((0 * NE + a) * TB + b) * 64 + lane];
+        float p1 = part[((1 * NE + a) * TB + b) * 64 + lane];
+        float p2 = part[((2 * NE + a) * TB + b) * 64 + lane];
+        float p3 = part[((3 * NE + a) * TB + b) * 64 + lane];
         float l = ((p0 + p1) + p2) + p3;
         if (e < E && bias) l = l + bias[e];
         lg[a] = e < E ? l : NEG;
@@ -166,22 +186,35 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     if (k < 1 || k > 2 || k > E) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: k must be 1 or 2 and <= E (k=%d E=%d)", k, E);
     if (E > 256) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: E=%d above 256", E);
     if (act_dtype != MOE_F16 && act_dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: act_dtype must be fp16 or bf16");
-    if (!aligned16(x)) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: x must be 16-byte aligned");
+    if (!aligned16(x) || !aligned16(wg)) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: x and wg must be 16-byte aligned");
     int EL = 8;
     while (EL < E && EL < 64) EL *= 2;
     const int NE = (E + 63) / 64;
-    const int ntok = (64 / EL) * kGateTB;
-    const size_t smem = (size_t)4 * ntok * kGateBlk * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * kGateTB * 64 * 4;
+    // four tokens per lane group, or one when that would leave most of the chip idle
+    const int tb = ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
+    const int ntok = (64 / EL) * tb;
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateBlk * E : 0);
+    const size_t smem = (size_t)4 * wave_halfs * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
     hipStream_t s = as_stream(stream);
-#define MOE_GATE_LAUNCH(BF, NEV)                                                                  \
-    hipLaunchKernelGGL((gate_kernel<BF, NEV>), grid, block, smem, s, xp, wp, bias, T, d, E, EL, k, \
-                       renormalize, expert_idx, expert_scale)
+#define MOE_GATE_LAUNCH(BF, NEV, TBV)                                                                  \
+    do {                                                                                               \
+        static bool raised = false;   /* more than 64 KB of dynamic LDS must be asked for once */       \
+        if (!raised) {                                                                                 \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV>),      \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);          \
+            raised = true;                                                                             \
+        }                                                                                              \
+        hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV>), grid, block, smem, s, xp, wp, bias, T, d, E,   \
+                           EL, k, renormalize, expert_idx, expert_scale);                              \
+    } while (0)
+#define MOE_GATE_TB(BF, NEV) do { if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4); else MOE_GATE_LAUNCH(BF, NEV, 1); } while (0)
     const bool bf = act_dtype == MOE_BF16;
-    if (NE == 1) { if (bf) MOE_GATE_LAUNCH(true, 1); else MOE_GATE_LAUNCH(false, 1); }
-    else if (NE == 2) { if (bf) MOE_GATE_LAUNCH(true, 2); else MOE_GATE_LAUNCH(false, 2); }
-    else { if (bf) MOE_GATE_LAUNCH(true, 4); else MOE_GATE_LAUNCH(false, 4); }
+    if (NE == 1) { if (bf) MOE_GATE_TB(true, 1); else MOE_GATE_TB(false, 1); }
+    else if (NE == 2) { if (bf) MOE_GATE_TB(true, 2); else MOE_GATE_TB(false, 2); }
+    else { if (bf) MOE_GATE_TB(true, 4); else MOE_GATE_TB(false, 4); }
+#undef MOE_GATE_TB
 #undef MOE_GATE_LAUNCH
     return check_launch("moe_gate_topk");
 }
