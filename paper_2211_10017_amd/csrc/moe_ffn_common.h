@@ -41,6 +41,14 @@ __device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_
 // 4-bit (Sec. 3.4.3): the eight codes of a dword sit in nibble positions 0,4,1,5,2,6,3,7, so
 // (x & 0x000f000f) | 0x64006400 is the pair (i0, i1) + 1024 and (x & 0x00f000f0) | 0x64006400 is
 // 16 * (i2, i3) + 1024; the latter is brought back with one fma: v/16 - (64 + 8).
+// A register-to-register move that the compiler cannot fold away.
+__device__ inline uint32_t opaque_copy(uint32_t x)
+{
+    uint32_t r;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+
 // (x & mask) | magic in one VALU instruction.  The compiler prefers two VOP2 instructions with
 // literal operands here (VOP3 cannot encode literals on this target), so the instruction is
 // spelled out, with mask and magic held in registers.

@@ -6,15 +6,20 @@
 // fragment block, see moe_common.h), converts the codes to FP16 with the 0x6400 trick and
 // feeds v_mfma_f32_32x32x16_f16; only the activations go through LDS, shared by the four
 // wavefronts of a block, each of which owns its own 64 output channels.
+#include <type_traits>
+
 #include "moe_ffn_common.h"
 
 namespace moe {
 
+#ifndef MOE_T_OCC
+#define MOE_T_OCC 2
+#endif
 constexpr int kLdsRow = 64 + 8;          // halfs per LDS row: 144-byte stride, conflict-free b128 reads
 constexpr int kTN = 2;                   // 32-channel tiles per wavefront
 
 template <int BITS, int SMODE, bool ABF16, int TM>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs p)
+__global__ __launch_bounds__(256, MOE_T_OCC) void grouped_gemm_kernel(GemmArgs p)
 {
     constexpr int BM = 32 * TM;
     constexpr int NW = BITS == 4 ? 1 : 2;             // 16-byte loads per tile per 64-deep K step
@@ -67,22 +72,60 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.0f;
 
-    uint4 ga[TM], gb[kTN][NW];
-    _Float16 gs[kTN];
-    auto load_global = [&](int kb) {
+    // Activations are fetched one K step ahead (they come from L2); packed weights and group
+    // scales two steps ahead, into two register sets used alternately (they come from HBM, and
+    // one step of MFMA work is shorter than that latency).
+    uint4 ga[TM], gb[2][kTN][NW];
+    _Float16 gs[2][kTN];
+    auto load_a = [&](int kb) {
 #pragma unroll
         for (int m = 0; m < TM; ++m) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kb * 64);
+    };
+    auto load_b = [&](int kb, auto slot_c) {
+        constexpr int SL = decltype(slot_c)::value;
 #pragma unroll
         for (int t = 0; t < kTN; ++t) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) gb[t][w] = b_ptr[t][(size_t)(kb * NW + w) * 64];
-            if (SMODE != SCALE_CHANNEL) gs[t] = __builtin_bit_cast(_Float16, s_ptr[t][(size_t)((kb * 64) / p.g) * N]);
+            for (int w = 0; w < NW; ++w) gb[SL][t][w] = b_ptr[t][(size_t)(kb * NW + w) * 64];
+            if (SMODE != SCALE_CHANNEL)
+                gs[SL][t] = __builtin_bit_cast(_Float16, s_ptr[t][(size_t)((kb * 64) / p.g) * N]);
         }
     };
 
-    load_global(0);
-    for (int kb = 0; kb < nk; ++kb) {
-        uint16_t *stage = lds_a[kb & 1];
+    load_a(0);
+    load_b(0, std::integral_constant<int, 0>{});
+    load_b(min(1, nk - 1), std::integral_constant<int, 1>{});
+    // Private copies of the two steps being computed.  They are taken (and the loads of the next
+    // two steps issued) once per pair of K steps, at the top of the loop body: at the loop edge
+    // every weight load is then at least a full step old, so the drain of the load counter that
+    // the compiler places at a loop head does not wait for fresh loads.
+    uint32_t raw2[2][kTN][NW * 4];
+    _Float16 sc2[2][kTN];
+    auto take_pair = [&](int kb) {
+        static_assert(true, "");
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+            for (int t = 0; t < kTN; ++t) {
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    // real register moves (opaque to the compiler): if it merged these copies with
+                    // the load registers, the refills would land elsewhere and have to be moved
+                    // back at the loop edge, i.e. waited for right after being issued
+                    raw2[sl][t][4 * w + 0] = opaque_copy(gb[sl][t][w].x); raw2[sl][t][4 * w + 1] = opaque_copy(gb[sl][t][w].y);
+                    raw2[sl][t][4 * w + 2] = opaque_copy(gb[sl][t][w].z); raw2[sl][t][4 * w + 3] = opaque_copy(gb[sl][t][w].w);
+                }
+                sc2[sl][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[sl][t])));
+            }
+        // (no branches around the loads: past the end they re-read the last step, which keeps the
+        // loop body free of joins and the load counter exact)
+        load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
+        load_b(min(kb + 3, nk - 1), std::integral_constant<int, 1>{});
+    };
+    auto k_step = [&](int kb, auto slot_c, auto live_c) {
+        constexpr int SL = decltype(slot_c)::value;
+        constexpr int LIVE = decltype(live_c)::value;    // row tiles of this block that hold rows      // = kb & 1: LDS stage and weight register set
+        uint16_t *stage = lds_a[SL];
         // ---- activations to LDS (bf16 rows are scaled by a power of two into FP16 range)
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
@@ -100,60 +143,101 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(GemmArgs p)
             }
             *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
         }
-        // ---- this step's weight fragments: unpack + convert in registers
-        uint32_t bw[kTN][4][4], bl[kTN][4][4];
+#if !defined(MOE_T_EXP_NOSYNC)
+        __syncthreads();
+#endif
+        uint32_t (&raw)[kTN][NW * 4] = raw2[SL];
+        _Float16 (&sc)[kTN] = sc2[SL];
+#if !defined(MOE_T_EXP_NOALOAD)
+        load_a(min(kb + 1, nk - 1));
+#endif
+        __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of this step's MFMAs
+
+        // unpack + convert one 16-deep step of weight fragments in registers
+        auto dequant_step = [&](int j, uint32_t (&bw)[kTN][4], uint32_t (&bl)[kTN][4]) {
 #pragma unroll
-        for (int t = 0; t < kTN; ++t) {
-            uint32_t raw[NW * 4];
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                raw[4 * w + 0] = gb[t][w].x; raw[4 * w + 1] = gb[t][w].y;
-                raw[4 * w + 2] = gb[t][w].z; raw[4 * w + 3] = gb[t][w].w;
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (BITS == 4) dequant4(raw[j], bw[t][j]);
-                else dequant8(raw[2 * j], raw[2 * j + 1], bw[t][j]);
+            for (int t = 0; t < kTN; ++t) {
+#if defined(MOE_T_EXP_NODEQ)
+                bw[t][0] = raw[t][j]; bw[t][1] = raw[t][j]; bw[t][2] = raw[t][j]; bw[t][3] = raw[t][j];
+#else
+                if (BITS == 4) dequant4(raw[t][j], bw[t]);
+                else dequant8(raw[t][2 * j], raw[t][2 * j + 1], bw[t]);
+#endif
                 if (SMODE == SCALE_GROUP) {
-                    const half2_t s2 = {gs[t], gs[t]};
+                    const half2_t s2 = {sc[t], sc[t]};
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) bw[t][j][q] = h2_bits(bits_h2(bw[t][j][q]) * s2);
+                    for (int q = 0; q < 4; ++q) bw[t][q] = h2_bits(bits_h2(bw[t][q]) * s2);
                 } else if (SMODE == SCALE_GROUP_SPLIT) {
                     // exact two-term weight: hi = fl(q*s'), lo = q*s' - hi, with s' = 256*s so
                     // that lo stays a normal FP16 number; the epilogue divides by 256
-                    const _Float16 s8 = gs[t] * (_Float16)256.0f;
+                    const _Float16 s8 = sc[t] * (_Float16)256.0f;
                     const half2_t s2 = {s8, s8};
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const half2_t qv = bits_h2(bw[t][j][q]);
+                        const half2_t qv = bits_h2(bw[t][q]);
                         const half2_t hi = qv * s2;
                         half2_t lo;
                         lo[0] = __builtin_fmaf16(qv[0], s2[0], -hi[0]);
                         lo[1] = __builtin_fmaf16(qv[1], s2[1], -hi[1]);
-                        bw[t][j][q] = h2_bits(hi);
-                        bl[t][j][q] = h2_bits(lo);
+                        bw[t][q] = h2_bits(hi);
+                        bl[t][q] = h2_bits(lo);
+                    }
+                }
+            }
+        };
+        // ---- MFMA over the four 16-deep steps of this K slab; the fragments of step j+1 are
+        // converted while the MFMAs of step j run (VALU work hides under the matrix pipe)
+#ifndef MOE_T_SKIP
+#define MOE_T_SKIP 0
+#endif
+#ifndef MOE_T_JIT
+#define MOE_T_JIT 1
+#endif
+#if MOE_T_JIT
+        uint32_t bw[2][kTN][4], bl[2][kTN][4];
+        dequant_step(0, bw[0], bl[0]);
+#else
+        uint32_t bw[4][kTN][4], bl[4][kTN][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dequant_step(j, bw[j], bl[j]);
+#endif
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#if MOE_T_JIT
+            if (j + 1 < 4) dequant_step(j + 1, bw[(j + 1) & 1], bl[(j + 1) & 1]);
+            constexpr int JM = 1;
+#else
+            constexpr int JM = 3;
+#endif
+#pragma unroll
+            for (int m = 0; m < TM; ++m) {
+                if (m < LIVE) {                         // row tiles past the expert's last row are skipped
+                    const half8_t af = *reinterpret_cast<const half8_t *>(
+                        stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
+#pragma unroll
+                    for (int t = 0; t < kTN; ++t) {
+                        acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), acc[m][t], 0, 0, 0);
+                        if (SMODE == SCALE_GROUP_SPLIT)
+                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[j & JM][t]), acc[m][t], 0, 0, 0);
                     }
                 }
             }
         }
-        __syncthreads();
-        if (kb + 1 < nk) load_global(kb + 1);
-        // ---- MFMA over the four 16-deep steps of this K slab
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int m = 0; m < TM; ++m) {
-                const half8_t af = *reinterpret_cast<const half8_t *>(
-                    stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
-#pragma unroll
-                for (int t = 0; t < kTN; ++t) {
-                    acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[t][j]), acc[m][t], 0, 0, 0);
-                    if (SMODE == SCALE_GROUP_SPLIT)
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[t][j]), acc[m][t], 0, 0, 0);
-                }
-            }
+    };
+    // The K loop exists once per number of live row tiles (the last tile of an expert usually
+    // holds few rows): a run-time test inside the loop would cut the MFMA stream into pieces.
+    auto k_loop = [&](auto live_c) {
+        for (int kb = 0; kb < nk; kb += 2) {
+            take_pair(kb);
+            k_step(kb, std::integral_constant<int, 0>{}, live_c);
+            if (kb + 1 < nk) k_step(kb + 1, std::integral_constant<int, 1>{}, live_c);
         }
-    }
+    };
+    const int live = (rows + 31) / 32;
+    if (TM == 1 || live == TM) k_loop(std::integral_constant<int, TM>{});
+    else if (TM >= 4 && live == 3) k_loop(std::integral_constant<int, 3>{});
+    else if (TM >= 2 && live == 2) k_loop(std::integral_constant<int, 2>{});
+    else k_loop(std::integral_constant<int, 1>{});
 
     // ---- epilogue: scale (per channel), bias, ReLU, store.  acc[m][t][i] is row
     // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
