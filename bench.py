@@ -24,6 +24,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the grouped GEMM, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# runs of this file (profiles/stream_gemm_c2_traffic.md): counter readings scaled by what the same
+# counters read for a plain 256 MiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 71.5e6}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
 
@@ -36,6 +41,9 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-bytes", type=float, default=float(1 << 30))
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run 5 plain device copies of 256 MiB: under `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` "
+                         "their counter reading calibrates the bytes-per-count of the GEMM's reading")
     return ap.parse_args()
 
 
@@ -117,6 +125,13 @@ def main():
     launches_per_ffn = 2                       # fc1 and fc2 are two launches of the same kernel
     launch_s = float(ffn_ms.mean()) * 1e-3 / launches_per_ffn
 
+    if args.traffic_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     off = layer.expert_offsets.cpu().numpy()
     active = int((np.diff(off) > 0).sum())
     g1 = w.d if w.group_size in (0, w.d) else w.group_size
@@ -133,7 +148,8 @@ def main():
         achieved = flops_ffn / launches_per_ffn / launch_s / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None}
-    roofline.update({"kernel": "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name)
+    roofline.update({"kernel": "stream_gemm_kernel" if roofline["bound"] == "hbm" else "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
                      "avg_launch_us": launch_s * 1e6, "ffn_us_median": float(np.median(ffn_ms)) * 1e3,
                      "ffn_us_min": float(ffn_ms.min()) * 1e3, "active_experts": active,
                      "algorithmic_bytes_per_step": int(bytes_ffn), "flops_per_step": flops_ffn,

@@ -13,6 +13,7 @@
 namespace moe {
 
 constexpr int kGateBlk = 128;    // feature block of one partial-sum turn
+constexpr int kGateWRow = kGateBlk + 8;   // LDS row of one expert's 128 gate weights (+16 bytes: conflict-free)
 
 template <bool BF16>
 __device__ inline float act_to_float(uint16_t v)
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 
     // wave-private staging areas: x [ntok][128] and (NE == 1) the gate weight block [128][E]
     constexpr bool WLDS = NE == 1;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateBlk * E : 0);
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateWRow * E : 0);
     uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * wave_halfs;
     uint16_t *ws = xs + (size_t)ntok * kGateBlk;
     float *part = reinterpret_cast<float *>(smem + (size_t)4 * wave_halfs * 2);  // [4][NE][TB][64]
@@ -75,9 +76,20 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
                     if (v0 + u * 64 + lane < nvec) tmp[u] = src[v0 + u * 64 + lane];
+                // written transposed, [expert][i], so that a lane later reads eight consecutive
+                // weights of its expert with one 16-byte LDS load
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (v0 + u * 64 + lane < nvec) reinterpret_cast<uint4 *>(ws)[v0 + u * 64 + lane] = tmp[u];
+                for (int u = 0; u < 8; ++u) {
+                    const int v = v0 + u * 64 + lane;
+                    if (v < nvec) {
+                        const uint32_t w4[4] = {tmp[u].x, tmp[u].y, tmp[u].z, tmp[u].w};
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) {
+                            const int el = v * 8 + q, i = el / E, e = el - i * E;
+                            ws[e * kGateWRow + i] = (uint16_t)(w4[q >> 1] >> (16 * (q & 1)));
+                        }
+                    }
+                }
             }
         }
         __syncthreads();
@@ -86,9 +98,15 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 #pragma unroll
             for (int a = 0; a < NE; ++a) {
                 const int e = min(a * 64 + le, E - 1);
+                if (WLDS) {
+                    const uint4 wr = *reinterpret_cast<const uint4 *>(ws + e * kGateWRow + i);
+                    const uint32_t w4[4] = {wr.x, wr.y, wr.z, wr.w};
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    wv[a][u] = act_to_float<BF16>(WLDS ? ws[(i + u) * E + e] : wg[(size_t)(i0 + i + u) * E + e]);
+                    for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>((uint16_t)(w4[u >> 1] >> (16 * (u & 1))));
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>(wg[(size_t)(i0 + i + u) * E + e]);
+                }
             }
 #pragma unroll
             for (int b = 0; b < TB; ++b) {
@@ -193,7 +211,7 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     // four tokens per lane group, or one when that would leave most of the chip idle
     const int tb = ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateBlk * E : 0);
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateWRow * E : 0);
     const size_t smem = (size_t)4 * wave_halfs * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;

@@ -5,9 +5,9 @@
 // wavefront counts its chunk per expert (integer LDS atomics: order-independent), the
 // counts are turned into per-chunk start positions by an exclusive scan over (expert, chunk),
 // and each wavefront then ranks its assignments in order with ballot-based match masks, so
-// the sort is stable and free of global atomics.  Small problems run as one block in a
-// single launch; larger ones take a count launch and a rank launch.  A third launch copies
-// the rows.
+// the sort is stable and free of global atomics.  Small problems (up to 4096 assignments) take
+// a single launch that also copies the rows; larger ones take a count launch, a rank launch and
+// a row-copy launch.
 #include "moe_common.h"
 
 namespace moe {
@@ -27,19 +27,26 @@ __device__ inline uint64_t match_key(int key, int key_bits)
     return m;
 }
 
-// FUSED: one block does count + scan + rank (grid of 1).  Otherwise PHASE selects count (0) or
-// rank (1), and the per-chunk histograms travel through `hist` [nwc][E].
+// FUSED: small problems, one launch: every block repeats count + scan + rank for all
+// assignments (cheap), keeps perm_src in LDS and then gathers its share of the rows; block 0
+// writes the index outputs.  Otherwise PHASE selects count (0) or rank (1), and the per-chunk
+// histograms travel through `hist` [nwc][E].
 template <bool FUSED, int PHASE>
 __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__restrict__ expert_idx,
                                                             int R, int E, int iters, int nwc,
                                                             int key_bits, int32_t *__restrict__ hist,
                                                             int32_t *__restrict__ perm_src,
                                                             int32_t *__restrict__ inv_perm,
-                                                            int32_t *__restrict__ offsets)
+                                                            int32_t *__restrict__ offsets,
+                                                            const uint4 *__restrict__ x, int k, int row_vec,
+                                                            uint4 *__restrict__ x_perm)
 {
-    extern __shared__ int32_t sm[];          // [4][E] per-wave counters, then [E] scratch
+    extern __shared__ int32_t sm[];          // [4][E] per-wave counters, [E] scratch, (FUSED) [R] perm_src
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wc = blockIdx.x * 4 + wave;    // wave-chunk id
+    const int blk = FUSED ? 0 : blockIdx.x;  // FUSED: every block plays block 0 of the index phase
+    const bool writer = !FUSED || blockIdx.x == 0;
+    int32_t *perm_l = sm + 5 * E;
+    const int wc = blk * 4 + wave;           // wave-chunk id
     const int CH = iters * 64;
     int32_t *cnt = sm + wave * E;
     int32_t *tot = sm + 4 * E;
@@ -53,7 +60,7 @@ __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__res
         }
         __syncthreads();
         if (!FUSED) {
-            for (int e = threadIdx.x; e < 4 * E; e += 256) hist[(size_t)blockIdx.x * 4 * E + e] = sm[e];
+            for (int e = threadIdx.x; e < 4 * E; e += 256) hist[(size_t)blk * 4 * E + e] = sm[e];
             return;
         }
     }
@@ -69,8 +76,8 @@ __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__res
         } else {
             for (int j = 0; j < nwc; ++j) {
                 const int v = hist[(size_t)j * E + e];
-                if (j < blockIdx.x * 4) before += v;
-                if (j >= blockIdx.x * 4 && j < blockIdx.x * 4 + 4) c[j - blockIdx.x * 4] = v;
+                if (j < blk * 4) before += v;
+                if (j >= blk * 4 && j < blk * 4 + 4) c[j - blk * 4] = v;
                 total += v;
             }
         }
@@ -95,12 +102,12 @@ __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__res
             if (e < E) tot[e] = carry + incl - v;
             carry += __shfl(incl, 63);
         }
-        if (blockIdx.x == 0 && lane == 0) offsets[E] = carry;
+        if (writer && blk == 0 && lane == 0) offsets[E] = carry;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += 256) {
         const int base = tot[e];
-        if (blockIdx.x == 0) offsets[e] = base;
+        if (writer && blk == 0) offsets[e] = base;
 #pragma unroll
         for (int w = 0; w < 4; ++w) sm[w * E + e] += base;
     }
@@ -117,12 +124,23 @@ __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__res
         int r = 0;
         if (live) {
             r = cnt[key] + rank;
-            perm_src[r] = a;
-            inv_perm[a] = r;
+            if (FUSED) perm_l[r] = a;
+            if (writer) {
+                perm_src[r] = a;
+                inv_perm[a] = r;
+            }
         }
         __syncthreads();                     // everyone has read cnt[] before the leaders bump it
         if (live && rank == 0) cnt[key] += __popcll(m);
         __syncthreads();
+    }
+    if (FUSED && x) {
+        // x_perm[r] = x[perm_src[r] / k] for this block's rows; one wavefront per row
+        for (int r = blockIdx.x * 4 + wave; r < R; r += gridDim.x * 4) {
+            const uint4 *src = x + (size_t)(perm_l[r] / k) * row_vec;
+            uint4 *dst = x_perm + (size_t)r * row_vec;
+            for (int v = lane; v < row_vec; v += 64) dst[v] = src[v];
+        }
     }
 }
 
@@ -184,18 +202,24 @@ extern "C" int moe_permute(const int32_t *expert_idx, const void *x, int act_dty
     hipStream_t s = as_stream(stream);
     const size_t smem = (size_t)5 * E * sizeof(int32_t);
     int32_t *hist = (int32_t *)workspace;
+    const int row_vec = (int)((size_t)d * elt / 16);
     if (nblocks == 1) {
-        hipLaunchKernelGGL((permute_index_kernel<true, 0>), dim3(1), dim3(256), smem, s, expert_idx, R, E,
-                           iters, 4, key_bits, hist, perm_src, inv_perm, expert_offsets);
-    } else {
-        hipLaunchKernelGGL((permute_index_kernel<false, 0>), dim3(nblocks), dim3(256), smem, s, expert_idx, R,
-                           E, iters, nblocks * 4, key_bits, hist, perm_src, inv_perm, expert_offsets);
-        hipLaunchKernelGGL((permute_index_kernel<false, 1>), dim3(nblocks), dim3(256), smem, s, expert_idx, R,
-                           E, iters, nblocks * 4, key_bits, hist, perm_src, inv_perm, expert_offsets);
+        // index and gather in one launch: up to 64 blocks share the row copies
+        int gb = x ? (R + 3) / 4 : 1;
+        gb = gb < 1 ? 1 : gb > 64 ? 64 : gb;
+        hipLaunchKernelGGL((permute_index_kernel<true, 0>), dim3(gb), dim3(256), smem + (size_t)R * sizeof(int32_t), s,
+                           expert_idx, R, E, iters, 4, key_bits, hist, perm_src, inv_perm, expert_offsets,
+                           (const uint4 *)x, k, row_vec, (uint4 *)x_perm);
+        return check_launch("moe_permute");
     }
+    hipLaunchKernelGGL((permute_index_kernel<false, 0>), dim3(nblocks), dim3(256), smem, s, expert_idx, R, E, iters,
+                       nblocks * 4, key_bits, hist, perm_src, inv_perm, expert_offsets, (const uint4 *)nullptr, k,
+                       row_vec, (uint4 *)nullptr);
+    hipLaunchKernelGGL((permute_index_kernel<false, 1>), dim3(nblocks), dim3(256), smem, s, expert_idx, R, E, iters,
+                       nblocks * 4, key_bits, hist, perm_src, inv_perm, expert_offsets, (const uint4 *)nullptr, k,
+                       row_vec, (uint4 *)nullptr);
     int rc = check_launch("moe_permute (index)");
     if (rc != MOE_OK || !x || R == 0) return rc;
-    const int row_vec = (int)((size_t)d * elt / 16);
     int gblocks = (R + 3) / 4;
     if (gblocks > 4096) gblocks = 4096;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(gblocks), dim3(256), 0, s, (const uint4 *)x, perm_src, R, k,

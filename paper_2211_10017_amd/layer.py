@@ -41,6 +41,7 @@ class MoEExpertLayer:
         self.ws_permute = torch.empty(B.moe_permute_workspace_bytes(T, k, E), dtype=torch.uint8, device=dev)
         self.ws_ffn = torch.empty(B.moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype),
                                   dtype=torch.uint8, device=dev)
+        self._plans = {}
 
     # -- offline: quantise one expert matrix from its fp32 master (which = 1 | 2) ------------
     def load_expert(self, which: int, e: int, w_fp32, q_canon_out=None):
@@ -73,7 +74,43 @@ class MoEExpertLayer:
         return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out)
 
     def forward(self, x):
-        self.gate(x)
-        self.permute(x)
-        self.ffn()
-        return self.combine()
+        """The four per-call entry points back to back.  The argument lists are marshalled once per
+        (input tensor, weight buffers, stream) and then replayed: in a decode-sized layer the
+        kernels are shorter than the time Python needs to rebuild them."""
+        opt = lambda t: 0 if t is None else t.data_ptr()  # noqa: E731
+        key = (x.data_ptr(), self.w1_packed.data_ptr(), self.w2_packed.data_ptr(), self.s1.data_ptr(),
+               self.s2.data_ptr(), self.wg.data_ptr(), opt(self.gate_bias), opt(self.b1), opt(self.b2),
+               torch.cuda.current_stream().cuda_stream)
+        calls = self._plans.get(key)
+        if calls is None:
+            calls = self._plans[key] = self._marshal(x, key[-1])
+            if len(self._plans) > 256:
+                self._plans.pop(next(iter(self._plans)))
+        for fn, args, name in calls:
+            rc = fn(*args)
+            if rc != 0:
+                B._check(rc, name)
+        return self.out
+
+    def _marshal(self, x, stream):
+        import ctypes
+        lib = B.load()
+        vp = ctypes.c_void_p
+        p = lambda t: None if t is None else vp(t.data_ptr())  # noqa: E731
+        if x.dtype != self.act_dtype or tuple(x.shape) != (self.T, self.d) or not x.is_contiguous() or not x.is_cuda:
+            raise B.MoeError("x must be a contiguous [T, d] CUDA tensor in the layer's activation dtype")
+        dt, ydt, odt = B._DT[self.act_dtype], B._DT[self.y_dtype], B._DT[self.out_dtype]
+        st = vp(stream)
+        return [
+            (lib.moe_gate_topk, (p(x), dt, p(self.wg), p(self.gate_bias), self.T, self.d, self.E, self.k,
+                                 int(self.renormalize), p(self.expert_idx), p(self.expert_scale), st), "moe_gate_topk"),
+            (lib.moe_permute, (p(self.expert_idx), p(x), dt, self.T, self.k, self.E, self.d, p(self.x_perm),
+                               p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
+                               self.ws_permute.numel(), st), "moe_permute"),
+            (lib.moe_grouped_ffn_wq, (p(self.x_perm), dt, p(self.expert_offsets), self.R, self.E, self.T, self.d,
+                                      self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1), p(self.b1),
+                                      p(self.w2_packed), p(self.s2), p(self.b2), p(self.y_perm), ydt,
+                                      p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq"),
+            (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), self.T, self.k, self.d,
+                               p(self.out), odt, st), "moe_combine"),
+        ]
