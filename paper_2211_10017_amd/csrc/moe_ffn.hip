@@ -75,6 +75,7 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     const int fit = stream_gemm_fit_rows(g.K);          // rows of an expert the streaming kernel holds in LDS
     if (stream_ok && max_rows <= 64) {
         g.row_hi = 0x7fffffff;                 // every expert streams, `fit` rows per block
+        if (stream_unrolled_supports(g.K, bits, smode)) return launch_stream_unrolled(g, bits, max_rows, s);
         return launch_stream_gemm(g, bits, smode, max_rows, s);
     }
     if (stream_ok && mean <= 96) {

@@ -30,6 +30,9 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
 int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hipStream_t s);
 bool stream_gemm_supports(int K, int bits, int smode);
 int stream_gemm_fit_rows(int K);
+bool stream_unrolled_supports(int K, int bits, int smode);
+int stream_unrolled_fit(int K, int max_rows);
+int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s);
 
 __device__ inline uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 __device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }

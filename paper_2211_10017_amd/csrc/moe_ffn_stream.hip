@@ -176,6 +176,239 @@ static void launch_stream(const GemmArgs &p, int tpw, dim3 grid, hipStream_t s)
     hipLaunchKernelGGL((stream_gemm_kernel<BITS>), grid, dim3(256), kStreamLds, s, p, tpw);
 }
 
+// ---- straight-line variant for slabs of at most 64 fragment blocks ------------------------------
+// With the K extent a compile-time constant the whole job of a wavefront (TPW slabs of KB blocks)
+// is unrolled into one basic block.  The ring of kRing loads is then refilled block by block: the
+// slot of the block just consumed is reloaded with the block kRing ahead, and because there is no
+// loop edge the compiler's wait before block b is "all but the 15 youngest loads", i.e. only the
+// load that block needs.  Every wavefront computes as its data trickles in, and the last wait of
+// the kernel is for a single block.
+constexpr int kStageVecs = 16;         // 16-byte vectors of activation rows one thread stages
+constexpr int kUnrolledFitCap = 16;    // rows per block: 16 rows of K = 1024 leave LDS for three blocks per CU
+
+//
+// KS = 4 splits the K range of a slab over the four wavefronts of the block (a slab of 64 blocks
+// would otherwise be one long, latency-bound stream per wavefront while most of the chip idles):
+// each wavefront accumulates a quarter of K, the four partial tiles meet in LDS and are added in a
+// fixed order.
+template <int BITS, int KB, int TPW, int KS>
+__global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int fit)
+{
+    constexpr int STEPS = BITS == 4 ? 4 : 2;
+    constexpr int FK = BITS == 4 ? 64 : 32;
+    constexpr int K = KB * FK;
+    constexpr int KBW = KB / KS;                        // fragment blocks of a slab one wavefront streams
+    constexpr int TOT = KBW * TPW;
+    constexpr int VPR = K / 8;                          // 16-byte vectors per row
+    constexpr int LDR = K + kRowPad;
+    extern __shared__ __align__(16) uint16_t lds_a[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int e = blockIdx.y, z = blockIdx.z;
+    const int N = p.N;
+    const int m = p.offsets[e + 1] - p.offsets[e];
+    if (m <= 0 || m > p.row_hi || z * fit >= m) return;   // same for the whole block
+    const int lo = p.offsets[e] + z * fit;
+    const int rows = min(fit, m - z * fit);
+    const int ntiles = N / 32;
+    const int tile0 = KS == 1 ? (blockIdx.x * 4 + wave) * TPW : blockIdx.x * TPW;
+    const int kq = KS == 1 ? 0 : wave;                  // this wavefront's part of K
+    const bool has = tile0 < ntiles;                    // ntiles is a multiple of TPW: all slabs or none
+    const int t0c = has ? tile0 : 0;
+    const uint4 *wbase = reinterpret_cast<const uint4 *>(p.wq + (size_t)e * packed_bytes_per_expert(K, N, BITS) +
+                                                         ((size_t)t0c * KB + kq * KBW) * kFragBytes) + lane;
+    // block b of this wavefront's stream, in fragment blocks from wbase
+    auto wofs = [](int b) { return (size_t)((b / KBW) * KB + b % KBW) * 64; };
+
+    // activation rows first (they are small and everything waits for them), then the scales, then
+    // the first ring of weights, in exactly this order: the scheduler barriers keep the compiler
+    // from moving the small loads behind the ring or shuffling the ring's order
+    const int total = rows * VPR;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *a_vec = reinterpret_cast<const u32x4 *>(p.a + (size_t)lo * K);
+    u32x4 av[kStageVecs];
+    static_for<0, kStageVecs>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
+    });
+    float cs[TPW], bias[TPW];
+    const __half *bias_or_scale = p.bias ? p.bias : p.scales;   // no branch around a load
+    const float bias_on = p.bias ? 1.0f : 0.0f;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int n = (t0c + t) * 32 + (lane & 31);
+        cs[t] = __half2float(p.scales[(size_t)e * N + n]);
+        bias[t] = __half2float(bias_or_scale[(size_t)e * N + n]) * bias_on;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    uint4 W[kRing];
+    static_for<0, kRing>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        W[i] = wbase[wofs(i)];
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    // vectors past the live rows (clamped reads above) land in a per-thread dump slot behind the rows
+    uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? 4 * 16 * 64 * 2 : 0) + threadIdx.x * 8;
+    static_for<0, kStageVecs>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const int idx = j * 256 + (int)threadIdx.x;
+        uint16_t *dst = idx < total ? lds_a + (idx / VPR) * LDR + (idx % VPR) * 8 : dump;
+        *reinterpret_cast<u32x4 *>(dst) = av[j];
+    });
+    __syncthreads();
+    if (!has) return;
+
+    const uint16_t *arow = lds_a + (size_t)min(lane & 31, rows - 1) * LDR + 8 * (lane >> 5) +
+                           kq * KBW * FK;               // clamped to a live row
+    float *part = reinterpret_cast<float *>(lds_a);    // KS = 4: [wave][16][64] partial tiles, over the rows once they are used up
+    uint4 A[2][STEPS];
+    float16_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    void *out_rows = reinterpret_cast<char *>(p.out) + (size_t)lo * N * (p.out_dtype == MOE_F32 ? 4 : 2);
+    auto fetch_a = [&](int slot, int kb) {
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) A[slot][j] = *reinterpret_cast<const uint4 *>(arow + kb * FK + 16 * j);
+    };
+    fetch_a(0, 0);
+    static_for<0, TOT>([&](auto bc) {
+        constexpr int b = decltype(bc)::value;
+        constexpr int kb = b % KBW, sl = b / KBW;
+        __builtin_amdgcn_sched_barrier(0);
+        if (b + 1 < TOT) fetch_a((b + 1) & 1, (b + 1) % KBW);
+        const uint32_t raw[4] = {W[b % kRing].x, W[b % kRing].y, W[b % kRing].z, W[b % kRing].w};
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+            uint32_t bw[4];
+            if (BITS == 4) dequant4(raw[j], bw);
+            else dequant8(raw[2 * j], raw[2 * j + 1], bw);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, A[b & 1][j]), frag_from(bw), acc, 0,
+                                                         0, 0);
+        }
+        if (b + kRing < TOT) W[b % kRing] = wbase[wofs(b + kRing)];
+        if (kb == KBW - 1) {
+            // slab finished: per-channel scale, bias, ReLU, store the live rows
+            const int n = (tile0 + sl) * 32 + (lane & 31);
+            const int rbase = 4 * (lane >> 5);
+            if constexpr (KS == 1) {
+                float v[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    v[q] = acc[q] * cs[sl] + bias[sl];
+                    if (p.relu) v[q] = fmaxf(v[q], 0.0f);
+                    acc[q] = 0.0f;
+                }
+                auto put = [&](auto *out) {             // rows rbase+0..3, +8..11, +16..19, +24..27
+                    size_t o = (size_t)rbase * N + n;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        if (rbase + 8 * (q >> 2) + (q & 3) < rows) {
+                            if constexpr (std::is_same<decltype(out), uint16_t *>::value) out[o] = to_bf16_rne(v[q]);
+                            else out[o] = (std::remove_pointer_t<decltype(out)>)v[q];
+                        }
+                        o += (q & 3) == 3 ? (size_t)5 * N : (size_t)N;
+                    }
+                };
+                if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
+                else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
+                else put(reinterpret_cast<uint16_t *>(out_rows));
+            } else {
+                // the four K-quarters meet in LDS; wavefront w then finishes accumulator registers
+                // 4w..4w+3 (rows rbase + 8w + 0..3), adding the quarters in the order 0, 1, 2, 3
+                static_assert(KS == 1 || TPW == 1, "the partial tiles overwrite the activation rows");
+                __syncthreads();                        // every wavefront is done with the rows
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    part[(wave * 16 + q) * 64 + lane] = acc[q];
+                    acc[q] = 0.0f;
+                }
+                __syncthreads();
+                float v[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float *src = part + ((wave * 4 + i) * 64 + lane);
+                    v[i] = ((src[0] + src[16 * 64]) + src[2 * 16 * 64]) + src[3 * 16 * 64];
+                    v[i] = v[i] * cs[sl] + bias[sl];
+                    if (p.relu) v[i] = fmaxf(v[i], 0.0f);
+                }
+                auto put = [&](auto *out) {
+                    size_t o = (size_t)(rbase + 8 * wave) * N + n;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (rbase + 8 * wave + i < rows) {
+                            if constexpr (std::is_same<decltype(out), uint16_t *>::value) out[o] = to_bf16_rne(v[i]);
+                            else out[o] = (std::remove_pointer_t<decltype(out)>)v[i];
+                        }
+                        o += N;
+                    }
+                };
+                if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
+                else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
+                else put(reinterpret_cast<uint16_t *>(out_rows));
+            }
+        }
+    });
+}
+
+template <int BITS, int KB, int TPW, int KS>
+static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_t s)
+{
+    constexpr int K = KB * (BITS == 4 ? 64 : 32);
+    // rows (KS = 4: or the partial tiles that later replace them) + the staging dump slots
+    int lds = fit * (K + kRowPad) * 2;
+    if (KS == 4 && lds < 4 * 16 * 64 * 4) lds = 4 * 16 * 64 * 4;
+    lds += 256 * 16;
+    static bool raised = false;
+    if (!raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+        raised = true;
+    }
+    const int ntiles = p.N / 32;
+    const int per_block = KS == 1 ? 4 * TPW : TPW;
+    dim3 grid((ntiles + per_block - 1) / per_block, p.E, (max_rows + fit - 1) / fit);
+    hipLaunchKernelGGL((stream_unrolled_kernel<BITS, KB, TPW, KS>), grid, dim3(256), lds, s, p, fit);
+}
+
+// Rows per block of the straight-line kernel: what one staging pass (kStageVecs vectors per
+// thread) and 64 KB of LDS hold.
+static int unrolled_fit_rows(int K, int max_rows)
+{
+    int fit = kStageVecs * 256 / (K / 8);
+    if (fit > kUnrolledFitCap) fit = kUnrolledFitCap;
+    if (fit > max_rows) fit = max_rows;
+    return fit < 1 ? 1 : fit;
+}
+
+bool stream_unrolled_supports(int K, int bits, int smode)
+{
+    const int fk = bits == 4 ? 64 : 32;
+    return smode == SCALE_CHANNEL && K % (fk * kRing) == 0 && K / fk <= 64;
+}
+
+int stream_unrolled_fit(int K, int max_rows) { return unrolled_fit_rows(K, max_rows); }
+
+int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s)
+{
+    const int kb = p.K / (bits == 4 ? 64 : 32);
+    const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
+    const int fit = unrolled_fit_rows(p.K, most);
+    if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: E=%d exceeds one launch", p.E);
+    // 16 blocks: one slab per wavefront; 64 blocks: one slab per block, K split over its wavefronts
+    if (bits == 4) {
+        if (kb == 16) launch_unrolled<4, 16, 1, 1>(p, fit, most, s);
+        else if (kb == 32) launch_unrolled<4, 32, 1, 1>(p, fit, most, s);
+        else if (kb == 48) launch_unrolled<4, 48, 1, 1>(p, fit, most, s);
+        else launch_unrolled<4, 64, 1, 4>(p, fit, most, s);
+    } else {
+        if (kb == 16) launch_unrolled<8, 16, 1, 1>(p, fit, most, s);
+        else if (kb == 32) launch_unrolled<8, 32, 1, 1>(p, fit, most, s);
+        else if (kb == 48) launch_unrolled<8, 48, 1, 1>(p, fit, most, s);
+        else launch_unrolled<8, 64, 1, 4>(p, fit, most, s);
+    }
+    return check_launch("moe_grouped_ffn_wq (straight-line streaming gemm)");
+}
+
 // The streaming kernel takes shapes whose slabs are whole rings of fragment blocks.
 bool stream_gemm_supports(int K, int bits, int smode)
 {

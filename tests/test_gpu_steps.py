@@ -142,6 +142,9 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False):
     ([32, 33, 1], 1024, 1024, 4, 0, "f16", torch.float32),
     ([7, 0, 16], 512, 2048, 8, 0, "f16", torch.float16),
     ([3, 4, 0, 0, 9, 2, 1, 6], 1024, 4096, 4, 0, "f16", torch.float32),
+    ([20, 0, 17, 5], 1024, 3072, 4, 0, "f16", torch.float16),
+    ([6, 11], 1536, 512, 8, 0, "f16", torch.float32),
+    ([3, 0, 12], 1024, 2048, 8, 0, "f16", torch.float16),
     ([31, 32, 33, 64, 65, 0, 129], 192, 320, 8, 0, "f16", torch.float16),
     ([100, 260, 7], 256, 512, 4, 128, "f16", torch.float16),
     ([17, 140], 512, 256, 8, 64, "f16", torch.float32),
@@ -160,6 +163,13 @@ def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
 def test_grouped_ffn_biases():
     _say("ffn with biases")
     got, want = _ffn_case([20, 45, 3], 128, 256, 8, 0, "f16", torch.float32, seed=5, with_bias=True)
+    max_abs, rel = error_metrics(got, want)
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+def test_grouped_ffn_biases_few_rows():
+    _say("ffn with biases, few rows")
+    got, want = _ffn_case([5, 9], 1024, 4096, 4, 0, "f16", torch.float32, seed=6, with_bias=True)
     max_abs, rel = error_metrics(got, want)
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
