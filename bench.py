@@ -149,7 +149,7 @@ def main():
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None}
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name)
-    roofline.update({"kernel": "stream_gemm_kernel" if roofline["bound"] == "hbm" else "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
+    roofline.update({"kernel": "stream_unrolled_kernel" if roofline["bound"] == "hbm" else "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
                      "avg_launch_us": launch_s * 1e6, "ffn_us_median": float(np.median(ffn_ms)) * 1e3,
                      "ffn_us_min": float(ffn_ms.min()) * 1e3, "active_experts": active,
                      "algorithmic_bytes_per_step": int(bytes_ffn), "flops_per_step": flops_ffn,

@@ -116,11 +116,15 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  * with fp16 MFMA and fp32 accumulation; the packed codes are unpacked and dequantised in
  * registers (never written back to memory).  Experts without rows cost no weight traffic.
  *
- *   x_perm [R,d] act_dtype; expert_offsets [E+1]
+ *   x_perm [R,d] act_dtype
+ *   expert_offsets [E+1] (device): a monotone partition of the R rows, offsets[0] = 0 and
+ *       offsets[E] = R, as moe_permute writes it.  The host cannot check it; the kernels force
+ *       every range into [0, R], so other contents give wrong results but no stray access.
  *   max_rows_per_expert: an upper bound on the rows any one expert receives, if the caller
- *       knows one (T is one: a token visits an expert at most once); 0 = unknown.  It only
- *       steers the choice between the weight-streaming and the tiled kernel: results do not
- *       depend on it, also when it is wrong.
+ *       knows one (T is one: a token visits an expert at most once); 0 = unknown (R is used).
+ *       It chooses between the weight-streaming kernels (bound <= 64) and the tiled kernel and
+ *       sizes the streaming launch, so it must be a true bound: rows of an expert beyond it
+ *       are not computed.
  *   w1_packed / w2_packed: q_packed from moe_quantize_experts for (E,d,F) / (E,F,d)
  *   s1 fp16 [E, d/g, F]; s2 fp16 [E, F/g, d]  (g = group_size, or K when group_size is 0)
  *   b1 [E,F] / b2 [E,d] fp16 or NULL

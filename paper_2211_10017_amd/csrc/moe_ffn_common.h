@@ -113,31 +113,65 @@ __device__ inline void store_out(void *out, int dtype, size_t o, float v)
     else reinterpret_cast<_Float16 *>(out)[o] = (_Float16)v;
 }
 
-// Finds the (expert, row tile) of tile slot `slot`: experts are walked 64 at a time, each lane
-// holding one expert's tile count, with a shuffle scan.  Every wavefront computes the same
-// answer; returns false when the slot is past the last tile.
-__device__ inline bool find_tile(const int32_t *offsets, int E, int BM, int row_lo, int slot,
-                                 int *e_out, int *row0, int *rows)
+// Work distribution of the tiled kernel.  A work item is (expert, column block, row tile); the
+// items are ordered expert-major, then by column block, row tile fastest, so that neighbours in
+// the order share a weight column block (row tiles of one expert) or an activation row tile
+// (column blocks of one expert).  The chip's workgroups go round-robin to its 8 XCDs, each with
+// an L2 of its own: workgroup id w runs on XCD w % 8, so XCD x is given the x-th contiguous
+// eighth of the order, walked in order by its workgroups w / 8.  What runs together on one XCD
+// then streams the same few row tiles and weight blocks through that XCD's L2.
+// Every wavefront computes the same answer; returns false when this workgroup has no item.
+constexpr int kXcds = 8;
+
+// Expert e's row range, forced into [0, R] and non-negative length: offsets that are not a
+// monotone partition of the R rows then give wrong results but no access outside the buffers.
+__device__ inline void expert_range(const int32_t *offsets, int e, int R, int *lo, int *hi)
+{
+    const int l = min(max(offsets[e], 0), R);
+    *lo = l;
+    *hi = min(max(offsets[e + 1], l), R);
+}
+
+__device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, int row_lo, int ncol, int wg,
+                                 int *e_out, int *col, int *row0, int *rows)
 {
     const int lane = threadIdx.x & 63;
+    int total = 0;                                     // row tiles of all experts
+    for (int e0 = 0; e0 < E; e0 += 64) {
+        const int e = e0 + lane;
+        int lo = 0, hi = 0;
+        if (e < E) expert_range(offsets, e, R, &lo, &hi);
+        const int m = hi - lo;
+        int tiles = m > row_lo ? (m + BM - 1) / BM : 0;
+        for (int off = 32; off > 0; off >>= 1) tiles += __shfl_xor(tiles, off);
+        total += tiles;
+    }
+    const long items = (long)total * ncol;
+    const long chunk = (items + kXcds - 1) / kXcds;
+    const long s = wg / kXcds;
+    const long item = (wg % kXcds) * chunk + s;
+    if (s >= chunk || item >= items) return false;
     int base = 0;
     for (int e0 = 0; e0 < E; e0 += 64) {
         const int e = e0 + lane;
         int lo = 0, hi = 0;
-        if (e < E) { lo = offsets[e]; hi = offsets[e + 1]; }
+        if (e < E) expert_range(offsets, e, R, &lo, &hi);
         const int tiles = hi - lo > row_lo ? (hi - lo + BM - 1) / BM : 0;
         int incl = tiles;
         for (int off = 1; off < 64; off <<= 1) {
             const int up = __shfl_up(incl, off);
             if (lane >= off) incl += up;
         }
-        const uint64_t hit = __ballot(base + incl > slot);
+        const uint64_t hit = __ballot((long)(base + incl) * ncol > item);
         if (hit) {
             const int src = __ffsll((unsigned long long)hit) - 1;
+            const int t_e = __shfl(tiles, src);
             const int excl = __shfl(incl - tiles, src);
-            const int mt = slot - base - excl;
+            const int local = (int)(item - (long)(base + excl) * ncol);
+            const int c = local / t_e, mt = local % t_e;
             const int lo_s = __shfl(lo, src), hi_s = __shfl(hi, src);
             *e_out = e0 + src;
+            *col = c;
             *row0 = lo_s + mt * BM;
             *rows = min(BM, hi_s - (lo_s + mt * BM));
             return true;

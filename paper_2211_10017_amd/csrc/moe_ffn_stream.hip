@@ -17,10 +17,7 @@
 namespace moe {
 
 constexpr int kRing = 16;             // weight fragment blocks in flight per wavefront
-#ifndef MOE_STREAM_LDS_KB
-#define MOE_STREAM_LDS_KB 72
-#endif
-constexpr int kStreamLds = MOE_STREAM_LDS_KB * 1024;  // LDS per block for an expert's activation rows (2 blocks per CU)
+constexpr int kStreamLds = 72 * 1024;  // LDS per block for an expert's activation rows (2 blocks per CU)
 constexpr int kRowPad = 8;             // halfs of padding per LDS row: rows start 4 banks apart
 
 // Rows of one expert that fit in LDS together, for the whole K range (at most one 32-row tile).
@@ -54,9 +51,11 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
     const int fit = stream_fit_rows(K);
     // blockIdx.z picks the group of `fit` rows (all rows at once for the few-row experts this
     // kernel is meant for; every further group streams the expert's weights again)
-    const int m = p.offsets[e + 1] - p.offsets[e];
+    int e_lo, e_hi;
+    expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
+    const int m = e_hi - e_lo;
     if (m <= 0 || m > p.row_hi || (int)blockIdx.z * fit >= m) return;   // same for the whole block
-    const int lo = p.offsets[e] + blockIdx.z * fit;
+    const int lo = e_lo + blockIdx.z * fit;
     const int rows = min(fit, m - (int)blockIdx.z * fit);
     const int KB = K / FK;                              // fragment blocks per slab, a multiple of kRing
     const int ntiles = N / 32;
@@ -206,9 +205,11 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int e = blockIdx.y, z = blockIdx.z;
     const int N = p.N;
-    const int m = p.offsets[e + 1] - p.offsets[e];
+    int e_lo, e_hi;
+    expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
+    const int m = e_hi - e_lo;
     if (m <= 0 || m > p.row_hi || z * fit >= m) return;   // same for the whole block
-    const int lo = p.offsets[e] + z * fit;
+    const int lo = e_lo + z * fit;
     const int rows = min(fit, m - z * fit);
     const int ntiles = N / 32;
     const int tile0 = KS == 1 ? (blockIdx.x * 4 + wave) * TPW : blockIdx.x * TPW;

@@ -12,26 +12,23 @@
 
 namespace moe {
 
-#ifndef MOE_T_OCC
-#define MOE_T_OCC 2
-#endif
 constexpr int kLdsRow = 64 + 8;          // halfs per LDS row: 144-byte stride, conflict-free b128 reads
 constexpr int kTN = 2;                   // 32-channel tiles per wavefront
 
 template <int BITS, int SMODE, bool ABF16, int TM>
-__global__ __launch_bounds__(256, MOE_T_OCC) void grouped_gemm_kernel(GemmArgs p)
+__global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 {
     constexpr int BM = 32 * TM;
     constexpr int NW = BITS == 4 ? 1 : 2;             // 16-byte loads per tile per 64-deep K step
     __shared__ __align__(16) uint16_t lds_a[2][BM * kLdsRow];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int e, row0, rows;
-    if (!find_tile(p.offsets, p.E, BM, p.row_lo, blockIdx.y, &e, &row0, &rows)) return;
-
     const int K = p.K, N = p.N;
+    int e, col, row0, rows;
+    if (!find_item(p.offsets, p.E, p.R, BM, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
+
     const int nk = K / 64;
-    const int ntile0 = (blockIdx.x * 4 + wave) * kTN;  // first 32-channel tile of this wavefront
+    const int ntile0 = (col * 4 + wave) * kTN;         // first 32-channel tile of this wavefront
     const int ntiles = N / 32;
     bool tile_ok[kTN];
 #pragma unroll
@@ -143,26 +140,18 @@ __global__ __launch_bounds__(256, MOE_T_OCC) void grouped_gemm_kernel(GemmArgs p
             }
             *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
         }
-#if !defined(MOE_T_EXP_NOSYNC)
         __syncthreads();
-#endif
         uint32_t (&raw)[kTN][NW * 4] = raw2[SL];
         _Float16 (&sc)[kTN] = sc2[SL];
-#if !defined(MOE_T_EXP_NOALOAD)
         load_a(min(kb + 1, nk - 1));
-#endif
         __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of this step's MFMAs
 
         // unpack + convert one 16-deep step of weight fragments in registers
         auto dequant_step = [&](int j, uint32_t (&bw)[kTN][4], uint32_t (&bl)[kTN][4]) {
 #pragma unroll
             for (int t = 0; t < kTN; ++t) {
-#if defined(MOE_T_EXP_NODEQ)
-                bw[t][0] = raw[t][j]; bw[t][1] = raw[t][j]; bw[t][2] = raw[t][j]; bw[t][3] = raw[t][j];
-#else
                 if (BITS == 4) dequant4(raw[t][j], bw[t]);
                 else dequant8(raw[t][2 * j], raw[t][2 * j + 1], bw[t]);
-#endif
                 if (SMODE == SCALE_GROUP) {
                     const half2_t s2 = {sc[t], sc[t]};
 #pragma unroll
@@ -187,28 +176,12 @@ __global__ __launch_bounds__(256, MOE_T_OCC) void grouped_gemm_kernel(GemmArgs p
         };
         // ---- MFMA over the four 16-deep steps of this K slab; the fragments of step j+1 are
         // converted while the MFMAs of step j run (VALU work hides under the matrix pipe)
-#ifndef MOE_T_SKIP
-#define MOE_T_SKIP 0
-#endif
-#ifndef MOE_T_JIT
-#define MOE_T_JIT 1
-#endif
-#if MOE_T_JIT
         uint32_t bw[2][kTN][4], bl[2][kTN][4];
         dequant_step(0, bw[0], bl[0]);
-#else
-        uint32_t bw[4][kTN][4], bl[4][kTN][4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) dequant_step(j, bw[j], bl[j]);
-#endif
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-#if MOE_T_JIT
             if (j + 1 < 4) dequant_step(j + 1, bw[(j + 1) & 1], bl[(j + 1) & 1]);
             constexpr int JM = 1;
-#else
-            constexpr int JM = 3;
-#endif
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
                 if (m < LIVE) {                         // row tiles past the expert's last row are skipped
@@ -301,8 +274,10 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
     const long most = (long)p.R / (p.row_lo + 1);               // experts that can exceed row_lo rows
     const long slots = (long)p.R / bm + (p.E < most ? p.E : most);
     if (slots == 0) return MOE_OK;
-    if (slots > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: %ld row tiles exceed one launch", slots);
-    dim3 grid((p.N + 255) / 256, (unsigned)slots);
+    const long ncol = (p.N + 255) / 256;
+    const long wgs = (slots * ncol + kXcds - 1) / kXcds * kXcds;   // upper bound of the work items, whole rounds of XCDs
+    if (wgs > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: %ld workgroups exceed one launch", wgs);
+    dim3 grid((unsigned)wgs);
     if (bits == 4) launch_mode<4>(p, smode, abf16, tm, grid, s);
     else launch_mode<8>(p, smode, abf16, tm, grid, s);
     return check_launch("moe_grouped_ffn_wq (gemm)");
