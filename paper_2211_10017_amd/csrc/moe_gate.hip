@@ -13,7 +13,7 @@
 namespace moe {
 
 constexpr int kGateBlk = 128;    // feature block of one partial-sum turn
-constexpr int kGateWRow = kGateBlk + 8;   // LDS row of one expert's 128 gate weights (+16 bytes: conflict-free)
+constexpr int kGateWRow = 64;     // LDS row of the staged gate-weight block: 64 experts' weights for one feature
 
 template <bool BF16>
 __device__ inline float act_to_float(uint16_t v)
@@ -22,6 +22,14 @@ __device__ inline float act_to_float(uint16_t v)
     __half h;
     *reinterpret_cast<uint16_t *>(&h) = v;
     return __half2float(h);
+}
+
+// acc + x * w in fp32 with both operands widened exactly (one v_fma_mix_f32 for fp16 inputs).
+template <bool BF16>
+__device__ inline float mac(uint16_t xb, uint16_t wb, float acc)
+{
+    if (BF16) return fmaf(__uint_as_float((uint32_t)xb << 16), __uint_as_float((uint32_t)wb << 16), acc);
+    return fmaf((float)__builtin_bit_cast(_Float16, xb), (float)__builtin_bit_cast(_Float16, wb), acc);
 }
 
 // With E <= 64 the 128 x E block of the gate weight that a wavefront needs per turn is copied
@@ -43,7 +51,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 
     // wave-private staging areas: x [ntok][128] and (NE == 1) the gate weight block [128][E]
     constexpr bool WLDS = NE == 1;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateWRow * E : 0);
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateWRow * kGateBlk : 0);
     uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * wave_halfs;
     uint16_t *ws = xs + (size_t)ntok * kGateBlk;
     float *part = reinterpret_cast<float *>(smem + (size_t)4 * wave_halfs * 2);  // [4][NE][TB][64]
@@ -54,59 +62,89 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 #pragma unroll
         for (int b = 0; b < TB; ++b) acc[a][b] = 0.0f;
 
+    const int e_shift = 31 - __builtin_clz(EL);
     const int nblk = (d + kGateBlk - 1) / kGateBlk;
     const int turns = (nblk + 3) / 4;             // same trip count for all four wavefronts
-    for (int turn = 0; turn < turns; ++turn) {
-        const int blk = turn * 4 + wave;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int XR = 2 * TB;                    // x vectors per lane per turn (ntok <= 8 * TB rows, 4 rows per pass)
+    constexpr int WR = WLDS ? 16 : 1;             // gate-weight vectors per lane per turn (128 x E halfs, E <= 64)
+    struct Staged { u32x4 x[XR]; u32x4 w[WR]; };
+
+    // global -> registers for one turn; nothing is waited for here
+    auto fetch = [&](int turn, Staged &st) {
+        const int blk = min(turn * 4 + wave, max(nblk - 1, 0));     // clamped: a turn past the end re-reads the last block
         const int i0 = blk * kGateBlk;
-        const int lim = blk < nblk ? min(kGateBlk, d - i0) : 0;     // multiple of 8
-        // stage x[t0 .. t0+ntok)[i0 .. i0+lim): 16 lanes per row, 16 bytes per lane
-        for (int row = lane >> 4; row < ntok; row += 4) {
+        const int lim = min(kGateBlk, d - i0);
+#pragma unroll
+        for (int r = 0; r < XR; ++r) {
+            const int row = (lane >> 4) + 4 * r;
             const int seg = (lane & 15) * 8;
-            const int t = min(t0 + row, T - 1);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (seg < lim) v = *reinterpret_cast<const uint4 *>(x + (size_t)t * d + i0 + seg);
-            *reinterpret_cast<uint4 *>(xs + row * kGateBlk + seg) = v;
+            const int t = min(t0 + min(row, ntok - 1), T - 1);
+            st.x[r] = *reinterpret_cast<const u32x4 *>(x + (size_t)t * d + i0 + min(seg, lim - 8));
         }
         if (WLDS) {
-            const uint4 *src = reinterpret_cast<const uint4 *>(wg + (size_t)i0 * E);
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(wg + (size_t)i0 * E);
             const int nvec = lim * E / 8;
-            for (int v0 = 0; v0 < nvec; v0 += 64 * 8) {          // eight loads in flight per lane
-                uint4 tmp[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    if (v0 + u * 64 + lane < nvec) tmp[u] = src[v0 + u * 64 + lane];
-                // written transposed, [expert][i], so that a lane later reads eight consecutive
-                // weights of its expert with one 16-byte LDS load
+            for (int u = 0; u < WR; ++u)
+                if (u * 64 < nvec) st.w[u] = src[min(u * 64 + lane, nvec - 1)];
+        }
+    };
+    // registers -> LDS: x rows as they are (zero past the block's end) and the weight block
+    auto stash = [&](int turn, const Staged &st) {
+        const int blk = turn * 4 + wave;
+        const int lim = blk < nblk ? min(kGateBlk, d - blk * kGateBlk) : 0;     // multiple of 8
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int v = v0 + u * 64 + lane;
-                    if (v < nvec) {
-                        const uint32_t w4[4] = {tmp[u].x, tmp[u].y, tmp[u].z, tmp[u].w};
+        for (int r = 0; r < XR; ++r) {
+            const int row = (lane >> 4) + 4 * r;
+            const int seg = (lane & 15) * 8;
+            if (row < ntok) {
+                u32x4 v = st.x[r];
+                if (seg >= lim) v = u32x4{0, 0, 0, 0};
+                *reinterpret_cast<u32x4 *>(xs + row * kGateBlk + seg) = v;
+            }
+        }
+        if (WLDS) {
+            // rows of the block keep their order, padded to 64 experts: [i][64]
+            const int nvec = lim * E / 8;
+#pragma unroll
+            for (int u = 0; u < WR; ++u) {
+                const int v = u * 64 + lane;
+                if (v < nvec) {
+                    int i, e;
+                    if (E == EL) {                               // power of two: shifts
+                        i = (v * 8) >> e_shift;
+                        e = (v * 8) & (E - 1);
+                    } else {                                     // one division per vector
+                        i = (v * 8) / E;
+                        e = v * 8 - i * E;
+                    }
+                    if ((E & 7) == 0) {
+                        *reinterpret_cast<u32x4 *>(ws + i * kGateWRow + e) = st.w[u];
+                    } else {
 #pragma unroll
                         for (int q = 0; q < 8; ++q) {
-                            const int el = v * 8 + q, i = el / E, e = el - i * E;
-                            ws[e * kGateWRow + i] = (uint16_t)(w4[q >> 1] >> (16 * (q & 1)));
+                            ws[i * kGateWRow + e] = (uint16_t)(st.w[u][q >> 1] >> (16 * (q & 1)));
+                            if (++e == E) { e = 0; ++i; }
                         }
                     }
                 }
             }
         }
-        __syncthreads();
-        for (int i = 0; i < lim; i += 8) {
-            float wv[NE][8];
+    };
+    auto compute = [&](int turn) {
+        const int blk = turn * 4 + wave;
+        const int i0 = blk * kGateBlk;
+        const int lim = blk < nblk ? min(kGateBlk, d - i0) : 0;
+#pragma unroll 2
+        for (int i = 0; i < lim; i += 8) {       // unrolled: several LDS reads in flight per wavefront
+            uint16_t wv[NE][8];
 #pragma unroll
             for (int a = 0; a < NE; ++a) {
                 const int e = min(a * 64 + le, E - 1);
-                if (WLDS) {
-                    const uint4 wr = *reinterpret_cast<const uint4 *>(ws + e * kGateWRow + i);
-                    const uint32_t w4[4] = {wr.x, wr.y, wr.z, wr.w};
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>((uint16_t)(w4[u >> 1] >> (16 * (u & 1))));
-                } else {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) wv[a][u] = act_to_float<BF16>(wg[(size_t)(i0 + i + u) * E + e]);
-                }
+                for (int u = 0; u < 8; ++u)
+                    wv[a][u] = WLDS ? ws[(i + u) * kGateWRow + e] : wg[(size_t)(i0 + i + u) * E + e];
             }
 #pragma unroll
             for (int b = 0; b < TB; ++b) {
@@ -114,13 +152,29 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
                 const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const float xv = act_to_float<BF16>((uint16_t)(r[u >> 1] >> (16 * (u & 1))));
+                    const uint16_t xb = (uint16_t)(r[u >> 1] >> (16 * (u & 1)));
 #pragma unroll
-                    for (int a = 0; a < NE; ++a) acc[a][b] = fmaf(xv, wv[a][u], acc[a][b]);
+                    for (int a = 0; a < NE; ++a) acc[a][b] = mac<BF16>(xb, wv[a][u], acc[a][b]);
                 }
             }
         }
-        __syncthreads();
+    };
+    // The loads of two turns are always in flight: with few tokens the whole kernel is one memory
+    // latency long, and two turns cover d = 1024.
+    // The staging areas are private to a wavefront, and LDS serves one wavefront's instructions in
+    // order, so a turn needs no barrier between its writes and reads.
+    Staged s0, s1;
+    fetch(0, s0);
+    fetch(1, s1);
+    for (int turn = 0; turn < turns; turn += 2) {
+        stash(turn, s0);
+        if (turn + 2 < turns) fetch(turn + 2, s0);
+        compute(turn);
+        if (turn + 1 < turns) {
+            stash(turn + 1, s1);
+            if (turn + 3 < turns) fetch(turn + 3, s1);
+            compute(turn + 1);
+        }
     }
 
 #pragma unroll
@@ -211,7 +265,7 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     // four tokens per lane group, or one when that would leave most of the chip idle
     const int tb = ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateWRow * E : 0);
+    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
     const size_t smem = (size_t)4 * wave_halfs * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
@@ -221,7 +275,7 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
         static bool raised = false;   /* more than 64 KB of dynamic LDS must be asked for once */       \
         if (!raised) {                                                                                 \
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV>),      \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);          \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);          \
             raised = true;                                                                             \
         }                                                                                              \
         hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV>), grid, block, smem, s, xp, wp, bias, T, d, E,   \
