@@ -146,7 +146,8 @@ def dequantize(q, s_bits, group_size: int = 0) -> np.ndarray:
 
 
 # ------------------------------------------------------------------ gate / routing
-def gate(x, wg, bias, k: int, renormalize: bool = True, return_logits: bool = False):
+def gate(x, wg, bias, k: int, renormalize: bool = True, return_logits: bool = False, finished=None):
+    """finished [T] (nonzero = pruned row, Sec. 3.5): such rows get expert index E and scale 0."""
     x, wg = _f32(x), _f32(wg)
     T, d = x.shape
     E = wg.shape[1]
@@ -155,13 +156,16 @@ def gate(x, wg, bias, k: int, renormalize: bool = True, return_logits: bool = Fa
     idx = np.empty((T, k), dtype=np.int32)
     scale = np.empty((T, k), dtype=np.float32)
     logits = np.empty((T, E), dtype=np.float32) if return_logits else None
-    _c().orc_gate(_p(x), _p(wg), None if b is None else _p(b), T, d, E, k, int(renormalize),
+    fin = None if finished is None else np.ascontiguousarray(finished, dtype=np.uint8)
+    _c().orc_gate(_p(x), _p(wg), None if b is None else _p(b), None if fin is None else _p(fin),
+                  T, d, E, k, int(renormalize),
                   _p(idx), _p(scale), None if logits is None else _p(logits))
     return (idx, scale, logits) if return_logits else (idx, scale)
 
 
 def permute(expert_idx, E: int):
-    """expert_idx int32 [T,k] -> (perm_src [R], inv_perm [R], offsets [E+1])."""
+    """expert_idx int32 [T,k] -> (perm_src [R], inv_perm [R], offsets [E+1]).
+    Index E marks pruned rows: they sort last and offsets[E] counts the active rows."""
     idx = _i32(expert_idx)
     T, k = idx.shape
     R = T * k
@@ -198,11 +202,12 @@ def expert_ffn(x_rows, w1dq, w2dq, act_dtype: int, b1=None, b2=None, return_h: b
     return (y, h) if return_h else y
 
 
-def combine(y_perm, inv_perm, scale, T: int, k: int) -> np.ndarray:
+def combine(y_perm, inv_perm, scale, T: int, k: int, active_rows=None) -> np.ndarray:
     y_perm, inv_perm, scale = _f32(y_perm), _i32(inv_perm), _f32(scale)
     d = y_perm.shape[1]
     out = np.empty((T, d), dtype=np.float32)
-    _c().orc_combine(_p(y_perm), _p(inv_perm), _p(scale), T, k, d, _p(out))
+    _c().orc_combine(_p(y_perm), _p(inv_perm), _p(scale), T, k, d,
+                     T * k if active_rows is None else int(active_rows), _p(out))
     return out
 
 
@@ -241,16 +246,17 @@ def grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size: int, act_dtype: int
 
 
 def moe_layer(x, wg, gate_bias, q1, s1, q2, s2, k: int, group_size: int, act_dtype: int,
-              renormalize: bool = True, y_dtype: int = F32, b1=None, b2=None):
-    """Gate -> permute -> grouped FFN -> combine; returns a dict of every intermediate."""
+              renormalize: bool = True, y_dtype: int = F32, b1=None, b2=None, finished=None):
+    """Gate -> permute -> grouped FFN -> combine; returns a dict of every intermediate.
+    finished [T]: rows pruned from the batch (Sec. 3.5); their output rows are zero."""
     E = q1.shape[0]
     T = x.shape[0]
-    idx, scale = gate(x, wg, gate_bias, k, renormalize)
+    idx, scale = gate(x, wg, gate_bias, k, renormalize, finished=finished)
     perm_src, inv_perm, offsets = permute(idx, E)
     x_perm = gather_rows(x, perm_src, k)
     y_perm = grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size, act_dtype, b1, b2)
     y_perm = round_to(y_perm, y_dtype)
-    out = combine(y_perm, inv_perm, scale, T, k)
+    out = combine(y_perm, inv_perm, scale, T, k, active_rows=int(offsets[E]))
     return dict(expert_idx=idx, expert_scale=scale, perm_src=perm_src, inv_perm=inv_perm,
                 expert_offsets=offsets, x_perm=x_perm, y_perm=y_perm, out=out)
 

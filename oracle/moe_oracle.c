@@ -210,7 +210,8 @@ void orc_int4_interleave8(const int8_t *in /*[8]*/, int8_t *out /*[8]*/)
  * partial sums, partial p taking the 128-element blocks b = i/128 with b % 4 == p, in
  * increasing i; then logit = ((p0 + p1) + p2) + p3, then + bias.
  */
-void orc_gate(const float *x, const float *wg, const float *bias, int T, int d, int E, int k,
+void orc_gate(const float *x, const float *wg, const float *bias, const uint8_t *finished /*[T] or NULL*/,
+              int T, int d, int E, int k,
               int renorm, int32_t *idx /*[T,k]*/, float *scale /*[T,k]*/,
               float *logits /*[T,E] or NULL*/)
 {
@@ -246,6 +247,10 @@ void orc_gate(const float *x, const float *wg, const float *bias, int T, int d, 
         }
         for (int j = 0; j < k; ++j)
             scale[(size_t)t * k + j] = (float)((k > 1 && renorm) ? psel[j] / psum : psel[j]);
+        /* Batch pruning (Sec. 3.5): a finished row gets an expert index past the real experts, so
+         * that the sort moves it behind every active row; it contributes nothing. */
+        if (finished && finished[t])
+            for (int j = 0; j < k; ++j) { idx[(size_t)t * k + j] = E; scale[(size_t)t * k + j] = 0.0f; }
         free(lg);
         free(taken);
     }
@@ -254,7 +259,9 @@ void orc_gate(const float *x, const float *wg, const float *bias, int T, int d, 
 /* ---------------------------------------------------------------- routing (Sec. 3.3)
  * The (expert, row) tuples, flattened token-major as a = t*k + j, are sorted by expert with
  * a stable sort; perm_src[r] = a, inv_perm[a] = r, offsets[e] = number of tuples whose
- * expert is < e (the start of expert e's sub-matrix), offsets[E] = T*k. */
+ * expert is < e (the start of expert e's sub-matrix).  Tuples of pruned rows carry the index E
+ * (Sec. 3.5) and sort behind all others: offsets[E] is the number of active rows (T*k without
+ * pruning), and only the rows before it are processed downstream. */
 void orc_permute(const int32_t *idx, int T, int k, int E, int32_t *perm_src, int32_t *inv_perm,
                  int32_t *offsets /*[E+1]*/)
 {
@@ -266,6 +273,8 @@ void orc_permute(const int32_t *idx, int T, int k, int E, int32_t *perm_src, int
             if (idx[a] == e) { perm_src[r] = a; inv_perm[a] = r; ++r; }
     }
     offsets[E] = r;
+    for (int a = 0; a < R; ++a)
+        if (idx[a] == E) { perm_src[r] = a; inv_perm[a] = r; ++r; }
 }
 
 void orc_gather_rows(const float *x, const int32_t *perm_src, int R, int k, int d, float *x_perm)
@@ -316,15 +325,18 @@ void orc_expert_ffn(const float *x /*[m,d]*/, int m, int d, int F,
  * Rows go back to their original order and are multiplied by expert_scale; with k > 1 the k
  * scaled rows of a token are added, j ascending. */
 void orc_combine(const float *y_perm /*[R,d]*/, const int32_t *inv_perm, const float *scale,
-                 int T, int k, int d, float *out /*[T,d]*/)
+                 int T, int k, int d, int active_rows /* rows at or past it are pruned: they add 0 */,
+                 float *out /*[T,d]*/)
 {
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < T; ++t)
         for (int n = 0; n < d; ++n) {
             double s = 0.0;
-            for (int j = 0; j < k; ++j)
-                s += (double)scale[(size_t)t * k + j] *
-                     (double)y_perm[(size_t)inv_perm[(size_t)t * k + j] * d + n];
+            for (int j = 0; j < k; ++j) {
+                const int r = inv_perm[(size_t)t * k + j];
+                if (r >= active_rows) continue;
+                s += (double)scale[(size_t)t * k + j] * (double)y_perm[(size_t)r * d + n];
+            }
             out[(size_t)t * d + n] = (float)s;
         }
 }

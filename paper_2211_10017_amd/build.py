@@ -49,5 +49,17 @@ def build_library(jobs: int = 8) -> str:
     return LIB
 
 
+def build_ceilings() -> str:
+    """Compile the stand-alone microbenchmark of the chip's achievable ceilings (microbench/ceilings)."""
+    src = os.path.join(HERE, "microbench", "ceilings.hip")
+    exe = os.path.join(HERE, "microbench", "ceilings")
+    flags = [f for f in HIPCC_FLAGS if f != "-fPIC"]
+    res = subprocess.run([_hipcc(), *flags, src, "-o", exe], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed for ceilings.hip:\n" + res.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     print(build_library())
+    print(build_ceilings())
