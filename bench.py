@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ring-bytes", type=float, default=float(1 << 30))
+    ap.add_argument("--finished", type=float, default=0.0,
+                    help="fraction of the rows marked finished (batch pruning, Sec. 3.5); 0 = the headline workload")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run 5 plain device copies of 256 MiB: under `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` "
                          "their counter reading calibrates the bytes-per-count of the GEMM's reading")
@@ -92,9 +94,14 @@ def main():
     for _ in range(ncopy - 1):
         ring.append(tuple(t.clone() for t in ring[0]))
 
+    finished = None
+    if args.finished > 0:
+        mask = np.random.default_rng(w.seed + 100).random(w.T) < args.finished
+        finished = torch.from_numpy(mask.astype(np.uint8)).to(dev)
+
     def step(i):
         layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
-        layer.forward(x)
+        layer.forward(x, finished)
 
     for i in range(args.warmup):
         step(i)
@@ -114,7 +121,7 @@ def main():
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for i in range(args.steps):
         layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
-        layer.gate(x)
+        layer.gate(x, finished)
         layer.permute(x)
         ev[i][0].record()
         layer.ffn()
@@ -134,11 +141,12 @@ def main():
 
     off = layer.expert_offsets.cpu().numpy()
     active = int((np.diff(off) > 0).sum())
+    active_rows = int(off[w.E])
     g1 = w.d if w.group_size in (0, w.d) else w.group_size
     g2 = w.F if w.group_size in (0, w.F) else w.group_size
     # algorithmic bytes: codes and fp16 scales of the experts that received rows
     bytes_ffn = active * (2 * w.d * w.F * w.bits // 8 + 2 * ((w.d // g1) * w.F + (w.F // g2) * w.d))
-    flops_ffn = 4.0 * w.R * w.d * w.F
+    flops_ffn = 4.0 * active_rows * w.d * w.F
     intensity = flops_ffn / bytes_ffn
     if intensity < MFMA_F16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
         achieved = bytes_ffn / launches_per_ffn / launch_s / 1e9
@@ -148,7 +156,7 @@ def main():
         achieved = flops_ffn / launches_per_ffn / launch_s / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name)
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name) if args.finished == 0 else None
     roofline.update({"kernel": "stream_unrolled_kernel" if roofline["bound"] == "hbm" else "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
                      "avg_launch_us": launch_s * 1e6, "ffn_us_median": float(np.median(ffn_ms)) * 1e3,
                      "ffn_us_min": float(ffn_ms.min()) * 1e3, "active_experts": active,
@@ -160,7 +168,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.act,
         "data": "synthetic", "config": {"workload": describe(w), "weights": "int%d" % w.bits,
-                                        "routed_rows": w.R, "cold_weights": ncopy > 1},
+                                        "routed_rows": w.R, "cold_weights": ncopy > 1,
+                                        **({"finished_fraction": args.finished, "active_rows": active_rows}
+                                           if args.finished > 0 else {})},
         "roofline": roofline,
     }
 

@@ -83,13 +83,18 @@ int moe_quantize_experts(const float *w, int E, int K, int N, int bits, int grou
  * round-robin to the four sums, each in increasing i), combined as ((p0+p1)+p2)+p3, then
  * the bias is added: this order is part of the contract, so routing is reproducible.
  *
+ * Sec. 3.5 (batch pruning): a row with finished[t] != 0 (a sentence that has ended) gets the
+ * expert index E, one past the real experts, and scale 0 in all its k slots; moe_permute sorts
+ * such rows behind every active row and nothing downstream touches them.
+ *
  *   x [T,d] act_dtype (MOE_F16 | MOE_BF16), wg [d,E] same dtype, bias [E] fp32 or NULL
+ *   finished [T] bytes (device) or NULL (no row is pruned)
  *   expert_idx [T,k] int32, expert_scale [T,k] fp32
  * Requires 1 <= k <= 2, k <= E <= 256, d >= 1.
  */
-int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias, int T, int d,
-                  int E, int k, int renormalize, int32_t *expert_idx, float *expert_scale,
-                  void *stream);
+int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias,
+                  const uint8_t *finished, int T, int d, int E, int k, int renormalize,
+                  int32_t *expert_idx, float *expert_scale, void *stream);
 
 /*
  * Sec. 3.3: routing.  The (expert, row) tuples are sorted by expert with a stable counting
@@ -101,7 +106,10 @@ int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bia
  *   inv_perm [R]          sorted position of assignment a
  *   expert_offsets [E+1]  rows of expert e are offsets[e] .. offsets[e+1]-1  (start of each
  *                         expert's sub-matrix); stays on the device
- * Entries of expert_idx outside [0,E) are a caller error (not checked).  d % 8 == 0.
+ * An entry of expert_idx equal to E marks a pruned row (Sec. 3.5): it is the last key of the
+ * sort, so these rows follow all others in perm_src / inv_perm, expert_offsets[E] is the number
+ * of active rows (R when nothing is pruned) and their x_perm rows are not written.  Other
+ * entries outside [0,E] are a caller error (not checked; they are treated as 0 or E).  d % 8 == 0.
  */
 size_t moe_permute_workspace_bytes(int T, int k, int E);
 int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, int k, int E,
@@ -144,10 +152,13 @@ int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_
  * Sec. 3.3, last step: rows return to their original order and are multiplied by
  * expert_scale:  out[t] = sum_j expert_scale[t,j] * y_perm[inv_perm[t*k+j]]  (fp32, j ascending).
  *   y_perm [R,d] y_dtype; out [T,d] out_dtype (each MOE_F16 | MOE_BF16 | MOE_F32); d % 8 == 0.
+ *   active_rows: device pointer to the number of active rows (expert_offsets + E) or NULL.
+ *       Terms whose row is at or past it belong to pruned tokens (Sec. 3.5): y_perm holds
+ *       nothing for them and they are left out, so a fully pruned token gets a zero row.
  */
 int moe_combine(const void *y_perm, int y_dtype, const int32_t *inv_perm,
-                const float *expert_scale, int T, int k, int d, void *out, int out_dtype,
-                void *stream);
+                const float *expert_scale, const int32_t *active_rows, int T, int k, int d,
+                void *out, int out_dtype, void *stream);
 
 #ifdef __cplusplus
 }

@@ -45,7 +45,7 @@ def load():
     lib.moe_quantize_experts.restype = i
     lib.moe_quantize_experts.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp]
     lib.moe_gate_topk.restype = i
-    lib.moe_gate_topk.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp, vp]
+    lib.moe_gate_topk.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, vp, vp, vp]
     lib.moe_permute_workspace_bytes.restype = sz
     lib.moe_permute_workspace_bytes.argtypes = [i, i, i]
     lib.moe_permute.restype = i
@@ -55,7 +55,7 @@ def load():
     lib.moe_grouped_ffn_wq.restype = i
     lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.moe_combine.restype = i
-    lib.moe_combine.argtypes = [vp, i, vp, vp, i, i, i, vp, i, vp]
+    lib.moe_combine.argtypes = [vp, i, vp, vp, vp, i, i, i, vp, i, vp]
     _lib = lib
     return lib
 
@@ -106,7 +106,7 @@ def moe_quantize_experts_into(w, bits, group_size, q_canon, scales, q_packed):
     _check(rc, "moe_quantize_experts")
 
 
-def moe_gate_topk(x, wg, bias, k: int, renormalize: bool = True, out=None):
+def moe_gate_topk(x, wg, bias, k: int, renormalize: bool = True, out=None, finished=None):
     T, d = x.shape
     E = wg.shape[1]
     if wg.dtype != x.dtype or wg.shape[0] != d:
@@ -117,7 +117,8 @@ def moe_gate_topk(x, wg, bias, k: int, renormalize: bool = True, out=None):
     else:
         idx, scale = out
     rc = load().moe_gate_topk(_ptr(x, (torch.float16, torch.bfloat16), "x"), _DT[x.dtype], _ptr(wg),
-                              _ptr(bias, torch.float32, "bias"), T, d, E, k, int(renormalize),
+                              _ptr(bias, torch.float32, "bias"), _ptr(finished, torch.uint8, "finished"),
+                              T, d, E, k, int(renormalize),
                               _ptr(idx, torch.int32), _ptr(scale, torch.float32), _stream())
     _check(rc, "moe_gate_topk")
     return idx, scale
@@ -172,12 +173,15 @@ def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int
     return y_perm
 
 
-def moe_combine(y_perm, inv_perm, expert_scale, T: int, k: int, out_dtype=torch.float32, out=None):
+def moe_combine(y_perm, inv_perm, expert_scale, T: int, k: int, out_dtype=torch.float32, out=None,
+                active_rows=None):
+    """active_rows: a one-element int32 view (expert_offsets[E:E+1]) when rows may be pruned."""
     d = y_perm.shape[1]
     if out is None:
         out = torch.empty((T, d), dtype=out_dtype, device=y_perm.device)
     rc = load().moe_combine(_ptr(y_perm), _DT[y_perm.dtype], _ptr(inv_perm, torch.int32, "inv_perm"),
-                            _ptr(expert_scale, torch.float32, "expert_scale"), T, k, d, _ptr(out),
+                            _ptr(expert_scale, torch.float32, "expert_scale"),
+                            _ptr(active_rows, torch.int32, "active_rows"), T, k, d, _ptr(out),
                             _DT[out.dtype], _stream())
     _check(rc, "moe_combine")
     return out

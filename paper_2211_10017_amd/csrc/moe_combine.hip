@@ -49,15 +49,19 @@ __device__ inline void store4(void *base, size_t idx4, const float v[4])
 template <int YDT, int ODT>
 __global__ __launch_bounds__(256) void combine_kernel(const void *__restrict__ y_perm,
                                                       const int32_t *__restrict__ inv_perm,
-                                                      const float *__restrict__ scale, int T, int k,
+                                                      const float *__restrict__ scale,
+                                                      const int32_t *__restrict__ active_rows, int T, int k,
                                                       int d4, void *__restrict__ out)
 {
+    // rows at or past *active_rows belong to pruned tokens (Sec. 3.5): never computed, they add nothing
+    const int active = active_rows ? *active_rows : 0x7fffffff;
     const size_t total = (size_t)T * d4;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
         const int t = (int)(i / d4), c = (int)(i % d4);
         float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int j = 0; j < k; ++j) {
             const int r = inv_perm[(size_t)t * k + j];
+            if (r >= active) continue;
             const float s = scale[(size_t)t * k + j];
             float v[4];
             load4<YDT>(y_perm, (size_t)r * d4 + c, v);
@@ -71,8 +75,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const void *__restrict__ y
 }  // namespace moe
 
 extern "C" int moe_combine(const void *y_perm, int y_dtype, const int32_t *inv_perm,
-                           const float *expert_scale, int T, int k, int d, void *out, int out_dtype,
-                           void *stream)
+                           const float *expert_scale, const int32_t *active_rows, int T, int k, int d,
+                           void *out, int out_dtype, void *stream)
 {
     using namespace moe;
     if (T == 0 && k > 0 && d > 0) return MOE_OK;         // empty buffers may be NULL
@@ -87,7 +91,7 @@ extern "C" int moe_combine(const void *y_perm, int y_dtype, const int32_t *inv_p
 #define MOE_COMBINE_CASE(Y, O)                                                                       \
     if (y_dtype == Y && out_dtype == O) {                                                            \
         hipLaunchKernelGGL((combine_kernel<Y, O>), dim3((unsigned)blocks), dim3(256), 0, s, y_perm,  \
-                           inv_perm, expert_scale, T, k, d4, out);                                   \
+                           inv_perm, expert_scale, active_rows, T, k, d4, out);                                   \
         return check_launch("moe_combine");                                                          \
     }
     MOE_COMBINE_CASE(MOE_F16, MOE_F16) MOE_COMBINE_CASE(MOE_F16, MOE_BF16) MOE_COMBINE_CASE(MOE_F16, MOE_F32)

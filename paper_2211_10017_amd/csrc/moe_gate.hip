@@ -37,7 +37,8 @@ __device__ inline float mac(uint16_t xb, uint16_t wb, float acc)
 template <bool BF16, int NE, int TB>
 __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ x,
                                                    const uint16_t *__restrict__ wg,
-                                                   const float *__restrict__ bias, int T, int d,
+                                                   const float *__restrict__ bias,
+                                                   const uint8_t *__restrict__ finished, int T, int d,
                                                    int E, int EL, int k, int renorm,
                                                    int32_t *__restrict__ expert_idx,
                                                    float *__restrict__ expert_scale)
@@ -229,7 +230,14 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     for (int off = EL >> 1; off > 0; off >>= 1) den += __shfl_xor(den, off);
 
     if (le == 0 && t < T) {
-        if (k == 1) {
+        if (finished && finished[t]) {
+            // batch pruning (Sec. 3.5): the row gets an expert index past the real experts, so the
+            // sort moves it behind every active row, and a zero scale
+            for (int j = 0; j < k; ++j) {
+                expert_idx[k * t + j] = E;
+                expert_scale[k * t + j] = 0.0f;
+            }
+        } else if (k == 1) {
             expert_idx[t] = sel[0];
             expert_scale[t] = 1.0f / den;
         } else {
@@ -246,9 +254,9 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 
 }  // namespace moe
 
-extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias, int T,
-                             int d, int E, int k, int renormalize, int32_t *expert_idx,
-                             float *expert_scale, void *stream)
+extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias,
+                             const uint8_t *finished, int T, int d, int E, int k, int renormalize,
+                             int32_t *expert_idx, float *expert_scale, void *stream)
 {
     using namespace moe;
     if (T == 0 && d > 0 && E > 0) return MOE_OK;         // nothing to route (empty buffers may be NULL)
@@ -278,7 +286,7 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);          \
             raised = true;                                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV>), grid, block, smem, s, xp, wp, bias, T, d, E,   \
+        hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV>), grid, block, smem, s, xp, wp, bias, finished, T, d, E,\
                            EL, k, renormalize, expert_idx, expert_scale);                              \
     } while (0)
 #define MOE_GATE_TB(BF, NEV) do { if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4); else MOE_GATE_LAUNCH(BF, NEV, 1); } while (0)

@@ -55,9 +55,9 @@ class MoEExpertLayer:
             setattr(self, name, getattr(other, name))
 
     # -- per call ---------------------------------------------------------------------------
-    def gate(self, x):
+    def gate(self, x, finished=None):
         return B.moe_gate_topk(x, self.wg, self.gate_bias, self.k, self.renormalize,
-                               out=(self.expert_idx, self.expert_scale))
+                               out=(self.expert_idx, self.expert_scale), finished=finished)
 
     def permute(self, x):
         return B.moe_permute(self.expert_idx, x, self.E,
@@ -71,19 +71,22 @@ class MoEExpertLayer:
                                     max_rows_per_expert=self.T)
 
     def combine(self):
-        return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out)
+        return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out,
+                             active_rows=self.expert_offsets[self.E:])
 
-    def forward(self, x):
+    def forward(self, x, finished=None):
         """The four per-call entry points back to back.  The argument lists are marshalled once per
         (input tensor, weight buffers, stream) and then replayed: in a decode-sized layer the
-        kernels are shorter than the time Python needs to rebuild them."""
+        kernels are shorter than the time Python needs to rebuild them.
+        finished: uint8 [T] on the device, nonzero for rows pruned from the batch (their output
+        rows are zero and their experts' weights are not read on their account)."""
         opt = lambda t: 0 if t is None else t.data_ptr()  # noqa: E731
-        key = (x.data_ptr(), self.w1_packed.data_ptr(), self.w2_packed.data_ptr(), self.s1.data_ptr(),
+        key = (x.data_ptr(), opt(finished), self.w1_packed.data_ptr(), self.w2_packed.data_ptr(), self.s1.data_ptr(),
                self.s2.data_ptr(), self.wg.data_ptr(), opt(self.gate_bias), opt(self.b1), opt(self.b2),
                torch.cuda.current_stream().cuda_stream)
         calls = self._plans.get(key)
         if calls is None:
-            calls = self._plans[key] = self._marshal(x, key[-1])
+            calls = self._plans[key] = self._marshal(x, finished, key[-1])
             if len(self._plans) > 256:
                 self._plans.pop(next(iter(self._plans)))
         for fn, args, name in calls:
@@ -92,17 +95,21 @@ class MoEExpertLayer:
                 B._check(rc, name)
         return self.out
 
-    def _marshal(self, x, stream):
+    def _marshal(self, x, finished, stream):
         import ctypes
         lib = B.load()
         vp = ctypes.c_void_p
         p = lambda t: None if t is None else vp(t.data_ptr())  # noqa: E731
         if x.dtype != self.act_dtype or tuple(x.shape) != (self.T, self.d) or not x.is_contiguous() or not x.is_cuda:
             raise B.MoeError("x must be a contiguous [T, d] CUDA tensor in the layer's activation dtype")
+        if finished is not None and (finished.dtype != torch.uint8 or finished.numel() != self.T
+                                     or not finished.is_contiguous() or not finished.is_cuda):
+            raise B.MoeError("finished must be a contiguous uint8 [T] CUDA tensor")
+        active = vp(self.expert_offsets.data_ptr() + 4 * self.E)
         dt, ydt, odt = B._DT[self.act_dtype], B._DT[self.y_dtype], B._DT[self.out_dtype]
         st = vp(stream)
         return [
-            (lib.moe_gate_topk, (p(x), dt, p(self.wg), p(self.gate_bias), self.T, self.d, self.E, self.k,
+            (lib.moe_gate_topk, (p(x), dt, p(self.wg), p(self.gate_bias), p(finished), self.T, self.d, self.E, self.k,
                                  int(self.renormalize), p(self.expert_idx), p(self.expert_scale), st), "moe_gate_topk"),
             (lib.moe_permute, (p(self.expert_idx), p(x), dt, self.T, self.k, self.E, self.d, p(self.x_perm),
                                p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
@@ -111,6 +118,6 @@ class MoEExpertLayer:
                                       self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1), p(self.b1),
                                       p(self.w2_packed), p(self.s2), p(self.b2), p(self.y_perm), ydt,
                                       p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq"),
-            (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), self.T, self.k, self.d,
+            (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), active, self.T, self.k, self.d,
                                p(self.out), odt, st), "moe_combine"),
         ]

@@ -63,6 +63,40 @@ def test_config(name, sample):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_config_with_pruned_rows(name):
+    """Batch pruning (Sec. 3.5) through the whole layer: finished rows come out as zero rows, the
+    rest as if the finished rows had not been in the batch."""
+    _say(f"config {name} with pruned rows")
+    prep = Prepared(W.WORKLOADS[name])
+    w, layer = prep.w, prep.layer
+    fin = (np.random.default_rng(w.seed + 100).random(w.T) < 0.4).astype(np.uint8)
+    res = oracle.moe_layer(prep.x, prep.wg, prep.bias, prep.q[1], prep.s[1], prep.q[2], prep.s[2], w.k,
+                           w.group_size, oracle_dtype_code(layer.act_dtype), renormalize=w.renormalize,
+                           y_dtype=oracle_dtype_code(layer.y_dtype), finished=fin)
+    out = layer.forward(prep.x_dev, finished=to_dev(fin, torch.uint8))
+    torch.cuda.synchronize()
+    assert np.array_equal(layer.expert_idx.cpu().numpy(), res["expert_idx"])
+    assert np.allclose(layer.expert_scale.cpu().numpy(), res["expert_scale"], rtol=1e-5, atol=1e-9)
+    assert np.array_equal(layer.expert_offsets.cpu().numpy(), res["expert_offsets"])
+    assert np.array_equal(layer.perm_src.cpu().numpy(), res["perm_src"])
+    assert np.array_equal(layer.inv_perm.cpu().numpy(), res["inv_perm"])
+    active = int(res["expert_offsets"][w.E])
+    assert 0 < active < w.R
+    assert np.array_equal(layer.x_perm.float().cpu().numpy()[:active], res["x_perm"][:active])
+    got = out.float().cpu().numpy()
+    assert not got[fin == 1].any()                               # exactly zero
+    max_abs, rel = error_metrics(got, res["out"])
+    _say(f"   {w.name} pruned: active rows {active} of {w.R}  max_abs={max_abs:.3e}  rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+    # and the un-pruned call afterwards is not disturbed by what the pruned one left behind
+    plain = layer.forward(prep.x_dev).float().cpu().numpy()
+    assert np.isfinite(plain).all() and np.abs(plain[fin == 1]).max() > 1e-3
+    del prep
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
 def test_config_c5_fp16_then_bf16():
     _say("config c5 fp16")
     prep = Prepared(W.WORKLOADS["c5"])

@@ -212,3 +212,57 @@ def test_calls_are_deterministic():
     got1, _ = _ffn_case([12, 90, 31], 256, 512, 4, 0, "f16", torch.float16, seed=77)
     got2, _ = _ffn_case([12, 90, 31], 256, 512, 4, 0, "f16", torch.float16, seed=77)
     assert np.array_equal(got1, got2)
+
+
+# ------------------------------------------------------------------ batch pruning (Sec. 3.5)
+@pytest.mark.parametrize("T,d,E,k", [(64, 1024, 32, 2), (130, 192, 3, 1), (77, 2048, 128, 2)])
+def test_gate_marks_finished_rows(T, d, E, k):
+    _say(f"gate with finished rows T={T} E={E} k={k}")
+    rng = np.random.default_rng(T + E)
+    x = to_dev(rng.standard_normal((T, d)).astype(np.float32), torch.float16)
+    wg = to_dev((rng.standard_normal((d, E)) * 0.02).astype(np.float32), torch.float16)
+    fin = (rng.random(T) < 0.35).astype(np.uint8)
+    oi, osc = oracle.gate(x.float().cpu().numpy(), wg.float().cpu().numpy(), None, k, True, finished=fin)
+    gi, gs = B.moe_gate_topk(x, wg, None, k, True, finished=to_dev(fin, torch.uint8))
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.allclose(gs.cpu().numpy(), osc, rtol=1e-5, atol=1e-9)
+    assert (oi[fin == 1] == E).all() and (oi[fin == 0] < E).all()
+
+
+@pytest.mark.parametrize("T,k,E,d", [(64, 2, 32, 1024), (300, 2, 13, 128), (5000, 2, 128, 64), (16384, 1, 64, 256),
+                                      (40, 1, 1, 64)])
+def test_permute_with_pruned_rows_bit_exact(T, k, E, d):
+    _say(f"permute with pruned rows T={T} k={k} E={E} d={d}")
+    rng = np.random.default_rng(T + E + 1)
+    idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    idx[rng.random(T) < 0.3] = E                                 # whole tokens pruned
+    x = rng.standard_normal((T, d)).astype(np.float16)
+    perm_src, inv_perm, off = oracle.permute(idx, E)
+    xp, ps, ip, of = B.moe_permute(to_dev(idx, torch.int32), to_dev(x, torch.float16), E)
+    torch.cuda.synchronize()
+    assert np.array_equal(of.cpu().numpy(), off)
+    assert np.array_equal(ps.cpu().numpy(), perm_src)
+    assert np.array_equal(ip.cpu().numpy(), inv_perm)
+    active = int(off[E])
+    assert 0 < active < T * k
+    assert np.array_equal(xp.cpu().numpy()[:active], x[perm_src[:active] // k])
+
+
+def test_combine_skips_pruned_rows():
+    _say("combine with pruned rows")
+    rng = np.random.default_rng(12)
+    T, k, d = 40, 2, 128
+    R = T * k
+    active = 51
+    y = rng.standard_normal((R, d)).astype(np.float32)
+    y[active:] = np.nan                                          # never computed: must not be read into the sum
+    inv = rng.permutation(R).astype(np.int32)
+    scale = rng.uniform(0, 1, (T, k)).astype(np.float32)
+    act_dev = torch.tensor([active], dtype=torch.int32, device=DEV)
+    out = B.moe_combine(to_dev(y, torch.float32), to_dev(inv, torch.int32), to_dev(scale, torch.float32), T, k,
+                        active_rows=act_dev)
+    torch.cuda.synchronize()
+    want = oracle.combine(y, inv, scale, T, k, active_rows=active)
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all() and np.allclose(got, want, rtol=1e-6, atol=1e-6)
