@@ -34,7 +34,7 @@ __device__ inline float mac(uint16_t xb, uint16_t wb, float acc)
 
 // With E <= 64 the 128 x E block of the gate weight that a wavefront needs per turn is copied
 // to LDS with 16-byte loads first (one latency per turn instead of one per row).
-template <bool BF16, int NE, int TB>
+template <bool BF16, int NE, int TB, int GM>
 __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ x,
                                                    const uint16_t *__restrict__ wg,
                                                    const float *__restrict__ bias,
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     const int nblk = (d + kGateBlk - 1) / kGateBlk;
     const int turns = (nblk + 3) / 4;             // same trip count for all four wavefronts
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr int XR = 2 * TB;                    // x vectors per lane per turn (ntok <= 8 * TB rows, 4 rows per pass)
+    constexpr int XR = GM * TB >= 4 ? GM * TB / 4 : 1;   // x vectors per lane per turn (ntok <= GM * TB rows, 4 rows per pass)
     constexpr int WR = WLDS ? 16 : 1;             // gate-weight vectors per lane per turn (128 x E halfs, E <= 64)
     struct Staged { u32x4 x[XR]; u32x4 w[WR]; };
 
@@ -147,15 +147,24 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
                 for (int u = 0; u < 8; ++u)
                     wv[a][u] = WLDS ? ws[(i + u) * kGateWRow + e] : wg[(size_t)(i0 + i + u) * E + e];
             }
+            // tokens in batches of up to eight: their rows are read first, then the features are
+            // walked with the tokens innermost, so that consecutive MACs are independent
+            constexpr int XB = TB < 8 ? TB : 8;
 #pragma unroll
-            for (int b = 0; b < TB; ++b) {
-                const uint4 raw = *reinterpret_cast<const uint4 *>(xs + (grp * TB + b) * kGateBlk + i);
-                const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
+            for (int b0 = 0; b0 < TB; b0 += XB) {
+                uint4 raw[XB];
+#pragma unroll
+                for (int b = 0; b < XB; ++b)
+                    raw[b] = *reinterpret_cast<const uint4 *>(xs + (grp * TB + b0 + b) * kGateBlk + i);
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const uint16_t xb = (uint16_t)(r[u >> 1] >> (16 * (u & 1)));
 #pragma unroll
-                    for (int a = 0; a < NE; ++a) acc[a][b] = mac<BF16>(xb, wv[a][u], acc[a][b]);
+                    for (int b = 0; b < XB; ++b) {
+                        const uint32_t r = u < 2 ? raw[b].x : u < 4 ? raw[b].y : u < 6 ? raw[b].z : raw[b].w;
+                        const uint16_t xb = (uint16_t)(r >> (16 * (u & 1)));
+#pragma unroll
+                        for (int a = 0; a < NE; ++a) acc[a][b0 + b] = mac<BF16>(xb, wv[a][u], acc[a][b0 + b]);
+                    }
                 }
             }
         }
@@ -184,9 +193,8 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
         for (int b = 0; b < TB; ++b) part[((wave * NE + a) * TB + b) * 64 + lane] = acc[a][b];
     __syncthreads();
 
-    // wavefront `wave` finishes token slot b = wave of every group
-    if (wave >= TB) return;
-    const int b = wave;
+    // wavefront `wave` finishes token slots b = wave, wave + 4, ... of every group
+    for (int b = wave; b < TB; b += 4) {
     const int t = t0 + grp * TB + b;
     float lg[NE];
     const float NEG = -INFINITY;
@@ -250,6 +258,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             expert_scale[2 * t + 1] = s1;
         }
     }
+    }   // token slots of this wavefront
 }
 
 }  // namespace moe
@@ -270,26 +279,34 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     int EL = 8;
     while (EL < E && EL < 64) EL *= 2;
     const int NE = (E + 63) / 64;
-    // four tokens per lane group, or one when that would leave most of the chip idle
-    const int tb = ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
+    // tokens per lane group: sixteen when every lane group is a whole wavefront and there are
+    // enough tokens to fill the chip that way (each block stages the whole gate weight, so more
+    // tokens per block mean less staging per token); else four; one when even that would leave
+    // most of the chip idle
+    const int tb = (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
     const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
     const size_t smem = (size_t)4 * wave_halfs * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
     hipStream_t s = as_stream(stream);
-#define MOE_GATE_LAUNCH(BF, NEV, TBV)                                                                  \
+#define MOE_GATE_LAUNCH(BF, NEV, TBV, GMV)                                                             \
     do {                                                                                               \
         static bool raised = false;   /* more than 64 KB of dynamic LDS must be asked for once */       \
         if (!raised) {                                                                                 \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV>),      \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV, GMV>), \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);          \
             raised = true;                                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV>), grid, block, smem, s, xp, wp, bias, finished, T, d, E,\
+        hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV, GMV>), grid, block, smem, s, xp, wp, bias, finished, T, d, E,\
                            EL, k, renormalize, expert_idx, expert_scale);                              \
     } while (0)
-#define MOE_GATE_TB(BF, NEV) do { if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4); else MOE_GATE_LAUNCH(BF, NEV, 1); } while (0)
+#define MOE_GATE_TB(BF, NEV)                                                                           \
+    do {                                                                                               \
+        if (tb == 16) MOE_GATE_LAUNCH(BF, NEV, 16, 1);                                                 \
+        else if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4, 8);                                              \
+        else MOE_GATE_LAUNCH(BF, NEV, 1, 8);                                                           \
+    } while (0)
     const bool bf = act_dtype == MOE_BF16;
     if (NE == 1) { if (bf) MOE_GATE_TB(true, 1); else MOE_GATE_TB(false, 1); }
     else if (NE == 2) { if (bf) MOE_GATE_TB(true, 2); else MOE_GATE_TB(false, 2); }
