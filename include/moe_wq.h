@@ -149,6 +149,29 @@ int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_
                        size_t workspace_bytes, void *stream);
 
 /*
+ * Table 1 (Sec. 4.1): throughput of one grouped GEMM  y[r] = x_perm[r] @ deq(W[e])  on about 40
+ * tokens spread over 1..32 active experts, with fp16, int8 and int4 weights.  This entry runs
+ * that single GEMM with the decode-sized streaming kernels of moe_grouped_ffn_wq:
+ *   bits 4 | 8: w_packed / scales from moe_quantize_experts (per-channel scales, group_size 0);
+ *   bits 16:    w_packed from moe_pack_fp16_experts (unquantised fp16 weights, scales ignored,
+ *               may be NULL) - the comparison's denominator;
+ *   native_convert != 0: the codes are converted with the chip's integer-to-float instructions
+ *               instead of the magic-number trick of Sec. 3.4.1 (same values; the route the
+ *               paper found slow), built for the table's shape only (K = 1024).
+ *   x_perm [R,K] fp16; expert_offsets [E+1] as for moe_grouped_ffn_wq; y [R,N] y_dtype.
+ * Requires at most 64 rows per expert (max_rows_per_expert, 0 = R), K % 64 == 0, N % 64 == 0 and
+ * a K the streaming kernel takes (a multiple of 16 fragment blocks, at most 64 of them: K = 1024
+ * .. 4096 for int4, 512 .. 2048 for int8, 256 .. 1024 for fp16); otherwise MOE_ERR_UNSUPPORTED.
+ *
+ * moe_pack_fp16_experts: w fp32 [E,K,N] (device) rounded to fp16 and stored in the fragment
+ * layout of the packed weights (E*K*N*2 bytes).  N % 32 == 0, K % 16 == 0.
+ */
+int moe_pack_fp16_experts(const float *w, int E, int K, int N, void *w_packed, void *stream);
+int moe_grouped_gemm_wq(const void *x_perm, const int32_t *expert_offsets, int R, int E,
+                        int max_rows_per_expert, int K, int N, int bits, int native_convert,
+                        const void *w_packed, const void *scales, void *y, int y_dtype, void *stream);
+
+/*
  * Sec. 3.3, last step: rows return to their original order and are multiplied by
  * expert_scale:  out[t] = sum_j expert_scale[t,j] * y_perm[inv_perm[t*k+j]]  (fp32, j ascending).
  *   y_perm [R,d] y_dtype; out [T,d] out_dtype (each MOE_F16 | MOE_BF16 | MOE_F32); d % 8 == 0.

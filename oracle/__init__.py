@@ -245,6 +245,23 @@ def grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size: int, act_dtype: int
     return (y, h) if return_h else y
 
 
+def grouped_gemm(x_perm, offsets, w_dq):
+    """One grouped GEMM (the operation Table 1 times): y[r] = x_perm[r] @ w_dq[e] for the rows r of
+    expert e, accumulated in fp64.  w_dq float32 [E,K,N] (dequantised or plain weights)."""
+    x_perm = _f32(x_perm)
+    R = x_perm.shape[0]
+    E, K, N = w_dq.shape
+    y = np.zeros((R, N), dtype=np.float64)
+    for e in range(E):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        for r in range(lo, hi):
+            acc = np.zeros(N, dtype=np.float64)
+            for i in range(K):
+                acc += float(x_perm[r, i]) * w_dq[e, i].astype(np.float64)
+            y[r] = acc
+    return y.astype(np.float32)
+
+
 def moe_layer(x, wg, gate_bias, q1, s1, q2, s2, k: int, group_size: int, act_dtype: int,
               renormalize: bool = True, y_dtype: int = F32, b1=None, b2=None, finished=None):
     """Gate -> permute -> grouped FFN -> combine; returns a dict of every intermediate.

@@ -20,7 +20,7 @@ _DT = {torch.float16: MOE_F16, torch.bfloat16: MOE_BF16, torch.float32: MOE_F32}
 
 EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
            "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
-           "moe_grouped_ffn_wq", "moe_combine"]
+           "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq"]
 
 _lib = None
 
@@ -54,6 +54,10 @@ def load():
     lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_ffn_wq.restype = i
     lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_pack_fp16_experts.restype = i
+    lib.moe_pack_fp16_experts.argtypes = [vp, i, i, i, vp, vp]
+    lib.moe_grouped_gemm_wq.restype = i
+    lib.moe_grouped_gemm_wq.argtypes = [vp, vp, i, i, i, i, i, i, i, vp, vp, vp, i, vp]
     lib.moe_combine.restype = i
     lib.moe_combine.argtypes = [vp, i, vp, vp, vp, i, i, i, vp, i, vp]
     _lib = lib
@@ -185,3 +189,26 @@ def moe_combine(y_perm, inv_perm, expert_scale, T: int, k: int, out_dtype=torch.
                             _DT[out.dtype], _stream())
     _check(rc, "moe_combine")
     return out
+
+
+def moe_pack_fp16_experts(w):
+    """w fp32 [E,K,N] -> fp16 weights in the fragment layout (uint8, E*K*N*2 bytes)."""
+    E, K, N = w.shape
+    packed = torch.empty(E * K * N * 2, dtype=torch.uint8, device=w.device)
+    rc = load().moe_pack_fp16_experts(_ptr(w, torch.float32, "w"), E, K, N, _ptr(packed), _stream())
+    _check(rc, "moe_pack_fp16_experts")
+    return packed
+
+
+def moe_grouped_gemm_wq(x_perm, expert_offsets, E: int, K: int, N: int, bits: int, w_packed, scales=None,
+                        native_convert: bool = False, y_dtype=None, y=None, max_rows_per_expert: int = 0):
+    """One grouped GEMM of the decode-sized case (Table 1): y[r] = x_perm[r] @ deq(W[e])."""
+    R = x_perm.shape[0]
+    if y is None:
+        y = torch.empty((R, N), dtype=y_dtype or x_perm.dtype, device=x_perm.device)
+    rc = load().moe_grouped_gemm_wq(_ptr(x_perm, torch.float16, "x_perm"), _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                    R, E, max_rows_per_expert, K, N, bits, int(native_convert),
+                                    _ptr(w_packed, torch.uint8, "w_packed"), _ptr(scales, torch.float16, "scales"),
+                                    _ptr(y), _DT[y.dtype], _stream())
+    _check(rc, "moe_grouped_gemm_wq")
+    return y

@@ -153,3 +153,36 @@ extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32
     }
     return run_gemm(g2, bits, grouped ? SCALE_GROUP : SCALE_CHANNEL, bf, max_rows, s);
 }
+
+// One grouped GEMM of the decode-sized case, for the comparison of Table 1 (fp16 / int8 / int4
+// weights, magic-number or native conversion).
+extern "C" int moe_grouped_gemm_wq(const void *x_perm, const int32_t *expert_offsets, int R, int E,
+                                   int max_rows_per_expert, int K, int N, int bits, int native_convert,
+                                   const void *w_packed, const void *scales, void *y, int y_dtype,
+                                   void *stream)
+{
+    using namespace moe;
+    if (!expert_offsets || !w_packed || (bits != 16 && !scales) || (R != 0 && (!x_perm || !y)))
+        return fail(MOE_ERR_INVALID_ARG, "moe_grouped_gemm_wq: NULL pointer");
+    if (R < 0 || E <= 0 || K <= 0 || N <= 0 || max_rows_per_expert < 0)
+        return fail(MOE_ERR_INVALID_ARG, "moe_grouped_gemm_wq: R >= 0, max_rows_per_expert >= 0 and E, K, N > 0 required");
+    if (K % 64 || N % 64) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_gemm_wq: K and N must be multiples of 64 (K=%d N=%d)", K, N);
+    if (bits != 4 && bits != 8 && bits != 16) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: bits must be 4, 8 or 16 (got %d)", bits);
+    if (y_dtype != MOE_F16 && y_dtype != MOE_BF16 && y_dtype != MOE_F32) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: unknown y_dtype %d", y_dtype);
+    if (E > 4096) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: E=%d above 4096", E);
+    const void *ptrs[] = {x_perm, w_packed, scales, y};
+    for (const void *q : ptrs)
+        if (!aligned16(q)) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_gemm_wq: buffers must be 16-byte aligned");
+    if (R == 0) return MOE_OK;
+    const int max_rows = max_rows_per_expert > 0 && max_rows_per_expert < R ? max_rows_per_expert : R;
+    if (max_rows > 64) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: only the decode-sized case (at most 64 rows per expert) is built");
+    if (!stream_unrolled_supports(K, bits, SCALE_CHANNEL))
+        return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: K=%d is not taken with bits=%d", K, bits);
+    GemmArgs g{};
+    g.a = (const uint16_t *)x_perm; g.offsets = expert_offsets; g.wq = (const uint8_t *)w_packed;
+    g.scales = (const __half *)scales; g.bias = nullptr; g.out = y; g.E = E; g.R = R; g.K = K; g.N = N; g.g = K;
+    g.out_dtype = y_dtype; g.relu = 0; g.row_lo = 0; g.row_hi = 0x7fffffff;
+    hipStream_t s = as_stream(stream);
+    if (bits == 16 || native_convert) return launch_stream_unrolled_variant(g, bits, native_convert != 0, max_rows, s);
+    return launch_stream_unrolled(g, bits, max_rows, s);
+}

@@ -33,6 +33,7 @@ int stream_gemm_fit_rows(int K);
 bool stream_unrolled_supports(int K, int bits, int smode);
 int stream_unrolled_fit(int K, int max_rows);
 int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s);
+int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s);
 
 __device__ inline uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 __device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
@@ -89,6 +90,33 @@ __device__ inline void dequant8(uint32_t w0, uint32_t w1, uint32_t out[4])
     out[1] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w0, 0x04030402u)) - sub);
     out[2] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w1, 0x04010400u)) - sub);
     out[3] = h2_bits(bits_h2(__builtin_amdgcn_perm(magic, w1, 0x04030402u)) - sub);
+}
+
+// The same conversions with the chip's integer-to-float instructions instead of the magic
+// number (the variant Sec. 3.4.1 measured as too slow on its hardware): extract the code, convert
+// to fp32, remove the offset, round to FP16.  Exact, like the magic-number route.
+__device__ inline void dequant4_native(uint32_t x, uint32_t out[4])
+{
+    // codes of MFMA index i sit in nibble position {0,4,1,5,2,6,3,7}[i]
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float lo = (float)((x >> (4 * q)) & 15u) - 8.0f;        // index 2q
+        const float hi = (float)((x >> (4 * q + 16)) & 15u) - 8.0f;   // index 2q + 1
+        const half2_t h = {(_Float16)lo, (_Float16)hi};
+        out[q] = h2_bits(h);
+    }
+}
+
+__device__ inline void dequant8_native(uint32_t w0, uint32_t w1, uint32_t out[4])
+{
+    const uint32_t w[2] = {w0, w1};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float lo = (float)((w[q >> 1] >> (16 * (q & 1))) & 255u) - 128.0f;
+        const float hi = (float)((w[q >> 1] >> (16 * (q & 1) + 8)) & 255u) - 128.0f;
+        const half2_t h = {(_Float16)lo, (_Float16)hi};
+        out[q] = h2_bits(h);
+    }
 }
 
 __device__ inline half8_t frag_from(const uint32_t w[4])

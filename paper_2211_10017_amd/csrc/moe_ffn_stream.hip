@@ -190,11 +190,16 @@ constexpr int kUnrolledFitCap = 16;    // rows per block: 16 rows of K = 1024 le
 // would otherwise be one long, latency-bound stream per wavefront while most of the chip idles):
 // each wavefront accumulates a quarter of K, the four partial tiles meet in LDS and are added in a
 // fixed order.
-template <int BITS, int KB, int TPW, int KS>
+//
+// BITS = 16 streams unquantised fp16 weights in the same fragment layout (one MFMA step per block;
+// the denominator of the Table 1 comparison).  NATIVE replaces the magic-number conversion by the
+// chip's integer-to-float conversion instructions (the variant Sec. 3.4.1 found too slow on its
+// hardware; kept for that comparison only).
+template <int BITS, int KB, int TPW, int KS, bool NATIVE = false>
 __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int fit)
 {
-    constexpr int STEPS = BITS == 4 ? 4 : 2;
-    constexpr int FK = BITS == 4 ? 64 : 32;
+    constexpr int STEPS = BITS == 4 ? 4 : BITS == 8 ? 2 : 1;
+    constexpr int FK = BITS == 4 ? 64 : BITS == 8 ? 32 : 16;
     constexpr int K = KB * FK;
     constexpr int KBW = KB / KS;                        // fragment blocks of a slab one wavefront streams
     constexpr int TOT = KBW * TPW;
@@ -233,12 +238,12 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
         av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
     });
     float cs[TPW], bias[TPW];
-    const __half *bias_or_scale = p.bias ? p.bias : p.scales;   // no branch around a load
+    const __half *bias_or_scale = p.bias ? p.bias : BITS == 16 ? reinterpret_cast<const __half *>(p.wq) : p.scales;   // no branch around a load
     const float bias_on = p.bias ? 1.0f : 0.0f;
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         const int n = (t0c + t) * 32 + (lane & 31);
-        cs[t] = __half2float(p.scales[(size_t)e * N + n]);
+        cs[t] = BITS == 16 ? 1.0f : __half2float(p.scales[(size_t)e * N + n]);
         bias[t] = __half2float(bias_or_scale[(size_t)e * N + n]) * bias_on;
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -281,7 +286,10 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
 #pragma unroll
         for (int j = 0; j < STEPS; ++j) {
             uint32_t bw[4];
-            if (BITS == 4) dequant4(raw[j], bw);
+            if (BITS == 16) { bw[0] = raw[0]; bw[1] = raw[1]; bw[2] = raw[2]; bw[3] = raw[3]; }
+            else if (NATIVE && BITS == 4) dequant4_native(raw[j], bw);
+            else if (NATIVE) dequant8_native(raw[2 * j], raw[2 * j + 1], bw);
+            else if (BITS == 4) dequant4(raw[j], bw);
             else dequant8(raw[2 * j], raw[2 * j + 1], bw);
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, A[b & 1][j]), frag_from(bw), acc, 0,
                                                          0, 0);
@@ -351,24 +359,24 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     });
 }
 
-template <int BITS, int KB, int TPW, int KS>
+template <int BITS, int KB, int TPW, int KS, bool NATIVE = false>
 static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_t s)
 {
-    constexpr int K = KB * (BITS == 4 ? 64 : 32);
+    constexpr int K = KB * (BITS == 4 ? 64 : BITS == 8 ? 32 : 16);
     // rows (KS = 4: or the partial tiles that later replace them) + the staging dump slots
     int lds = fit * (K + kRowPad) * 2;
     if (KS == 4 && lds < 4 * 16 * 64 * 4) lds = 4 * 16 * 64 * 4;
     lds += 256 * 16;
     static bool raised = false;
     if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         raised = true;
     }
     const int ntiles = p.N / 32;
     const int per_block = KS == 1 ? 4 * TPW : TPW;
     dim3 grid((ntiles + per_block - 1) / per_block, p.E, (max_rows + fit - 1) / fit);
-    hipLaunchKernelGGL((stream_unrolled_kernel<BITS, KB, TPW, KS>), grid, dim3(256), lds, s, p, fit);
+    hipLaunchKernelGGL((stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE>), grid, dim3(256), lds, s, p, fit);
 }
 
 // Rows per block of the straight-line kernel: what one staging pass (kStageVecs vectors per
@@ -383,11 +391,27 @@ static int unrolled_fit_rows(int K, int max_rows)
 
 bool stream_unrolled_supports(int K, int bits, int smode)
 {
-    const int fk = bits == 4 ? 64 : 32;
+    const int fk = bits == 4 ? 64 : bits == 8 ? 32 : 16;
     return smode == SCALE_CHANNEL && K % (fk * kRing) == 0 && K / fk <= 64;
 }
 
 int stream_unrolled_fit(int K, int max_rows) { return unrolled_fit_rows(K, max_rows); }
+
+// The Table 1 variants: fp16 weights (bits = 16) and the native integer-to-float conversion.
+int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s)
+{
+    const int kb = p.K / (bits == 4 ? 64 : bits == 8 ? 32 : 16);
+    const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
+    const int fit = unrolled_fit_rows(p.K, most);
+    if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: E=%d exceeds one launch", p.E);
+    if (bits == 16 && kb == 64 && !native) launch_unrolled<16, 64, 1, 4>(p, fit, most, s);
+    else if (bits == 16 && kb == 32 && !native) launch_unrolled<16, 32, 1, 1>(p, fit, most, s);
+    else if (bits == 16 && kb == 16 && !native) launch_unrolled<16, 16, 1, 1>(p, fit, most, s);
+    else if (bits == 4 && kb == 16 && native) launch_unrolled<4, 16, 1, 1, true>(p, fit, most, s);
+    else if (bits == 8 && kb == 32 && native) launch_unrolled<8, 32, 1, 1, true>(p, fit, most, s);
+    else return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: no kernel for bits=%d K=%d convert=%d", bits, p.K, (int)native);
+    return check_launch("moe_grouped_gemm_wq");
+}
 
 int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s)
 {

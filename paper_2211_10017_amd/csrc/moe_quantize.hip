@@ -92,7 +92,40 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
     }
 }
 
+// Unquantised fp16 weights in the fragment layout (one MFMA step, 16 K values, per 1 KB block):
+// lane l of block (nb, kb) holds w[16 kb + 8 (l >> 5) + 0..7][32 nb + (l & 31)].
+__global__ __launch_bounds__(256) void pack_f16_kernel(const float *__restrict__ w, int K, int N,
+                                                       uint16_t *__restrict__ packed)
+{
+    const int e = blockIdx.z, kb = blockIdx.y;
+    const int nb = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (nb >= N / 32) return;
+    const int n = nb * 32 + (lane & 31), k0 = kb * 16 + 8 * (lane >> 5);
+    uint16_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const __half h = __float2half_rn(w[((size_t)e * K + k0 + i) * N + n]);
+        v[i] = *reinterpret_cast<const uint16_t *>(&h);
+    }
+    uint16_t *dst = packed + (size_t)e * K * N + (((size_t)nb * (K / 16) + kb) * 64 + lane) * 8;
+    *reinterpret_cast<uint4 *>(dst) = make_uint4(v[0] | (uint32_t)v[1] << 16, v[2] | (uint32_t)v[3] << 16,
+                                                 v[4] | (uint32_t)v[5] << 16, v[6] | (uint32_t)v[7] << 16);
+}
+
 }  // namespace moe
+
+extern "C" int moe_pack_fp16_experts(const float *w, int E, int K, int N, void *w_packed, void *stream)
+{
+    using namespace moe;
+    if (!w || !w_packed) return fail(MOE_ERR_INVALID_ARG, "moe_pack_fp16_experts: NULL pointer");
+    if (E <= 0 || K <= 0 || N <= 0) return fail(MOE_ERR_INVALID_ARG, "moe_pack_fp16_experts: E, K, N must be positive");
+    if (N % 32 || K % 16) return fail(MOE_ERR_INVALID_ARG, "moe_pack_fp16_experts: need N %% 32 == 0 and K %% 16 == 0 (K=%d N=%d)", K, N);
+    if (E > 65535 || K / 16 > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_pack_fp16_experts: too many experts or K blocks for one launch");
+    if (!aligned16(w) || !aligned16(w_packed)) return fail(MOE_ERR_INVALID_ARG, "moe_pack_fp16_experts: buffers must be 16-byte aligned");
+    dim3 grid((N / 32 + 3) / 4, K / 16, E);
+    hipLaunchKernelGGL(pack_f16_kernel, grid, dim3(256), 0, as_stream(stream), w, K, N, (uint16_t *)w_packed);
+    return check_launch("moe_pack_fp16_experts");
+}
 
 extern "C" int moe_quantize_experts(const float *w, int E, int K, int N, int bits, int group_size,
                                     void *q_canon, void *scales, void *q_packed, void *stream)

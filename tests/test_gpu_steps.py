@@ -266,3 +266,32 @@ def test_combine_skips_pruned_rows():
     want = oracle.combine(y, inv, scale, T, k, active_rows=active)
     got = out.cpu().numpy()
     assert np.isfinite(got).all() and np.allclose(got, want, rtol=1e-6, atol=1e-6)
+
+
+# ------------------------------------------------------------------ single grouped GEMM (Table 1)
+@pytest.mark.parametrize("bits,native,K,N", [(4, False, 1024, 256), (4, True, 1024, 256), (8, False, 1024, 192),
+                                              (8, True, 1024, 192), (16, False, 1024, 256), (16, False, 512, 128),
+                                              (16, False, 256, 64), (4, False, 4096, 128), (8, False, 512, 320)])
+def test_grouped_gemm_matches_oracle(bits, native, K, N):
+    _say(f"grouped gemm bits={bits} native={native} K={K} N={N}")
+    rng = np.random.default_rng(bits + K + N + native)
+    rows = [3, 0, 5, 1, 17, 2]
+    E = len(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    x = to_dev(rng.standard_normal((int(off[-1]), K)).astype(np.float32), torch.float16)
+    w = (rng.standard_normal((E, K, N)) * 0.05).astype(np.float32)
+    if bits == 16:
+        packed = B.moe_pack_fp16_experts(to_dev(w, torch.float32))
+        scales = None
+        w_dq = w.astype(np.float16).astype(np.float32)
+    else:
+        _, scales, packed = B.moe_quantize_experts(to_dev(w, torch.float32), bits, 0, want_canon=False)
+        q, s = oracle.quantize(w, bits, 0)
+        w_dq = oracle.dequantize(q, s, 0)
+    y = B.moe_grouped_gemm_wq(x, to_dev(off, torch.int32), E, K, N, bits, packed, scales, native_convert=native,
+                              y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = oracle.grouped_gemm(x.float().cpu().numpy(), off, w_dq)
+    max_abs, rel = error_metrics(y.cpu().numpy(), want)
+    _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= 1e-5          # exact weights on both sides: only the fp32 summation order differs

@@ -135,3 +135,19 @@ def test_combine_closed_form():
     scale = np.array([[0.25, 0.75], [1.0, 0.0], [0.5, 0.5]], dtype=np.float32)
     out = oracle.combine(y, inv, scale, T, k)
     assert np.array_equal(out[:, 0], np.array([0.25 * 5 + 0, 1.0, 2.5], dtype=np.float32))
+
+
+def test_grouped_gemm_against_library_matmul():
+    """The single grouped GEMM (Table 1's operation) against a library fp64 matmul per expert;
+    K != N and uneven row counts, so a transposed operand or a shifted offset cannot pass."""
+    rng = np.random.default_rng(21)
+    rows = [3, 0, 5, 1]
+    K, N = 24, 40
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    x = rng.standard_normal((off[-1], K)).astype(np.float16).astype(np.float32)
+    w = rng.standard_normal((len(rows), K, N)).astype(np.float32)
+    got = oracle.grouped_gemm(x, off, w)
+    for e in range(len(rows)):
+        want = x[off[e]:off[e + 1]].astype(np.float64) @ w[e].astype(np.float64)
+        assert np.allclose(got[off[e]:off[e + 1]], want, rtol=1e-6, atol=1e-6)
+    assert np.abs(got).max() > 1.0
