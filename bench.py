@@ -103,6 +103,8 @@ def main():
         layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
         layer.forward(x, finished)
 
+    for i in range(ncopy):                # first use of every ring copy marshals its argument lists: not a step
+        step(i)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

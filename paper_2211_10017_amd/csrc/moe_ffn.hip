@@ -73,9 +73,14 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     const bool stream_ok = !bf && stream_gemm_supports(g.K, bits, smode);
     const int mean = (g.R + g.E - 1) / g.E;
     const int fit = stream_gemm_fit_rows(g.K);          // rows of an expert the streaming kernel holds in LDS
-    if (stream_ok && max_rows <= 64) {
+    // Few rows per expert on average and a bound that needs at most 16 row groups: every expert
+    // streams its weights once per group of `fit` rows (the groups of one expert run together and
+    // share the stream in L2), which beats row tiles whose K loops would run on a handful of blocks.
+    const bool unrolled = stream_ok && stream_unrolled_supports(g.K, bits, smode);
+    const bool few = unrolled && mean <= 32 && max_rows <= 16 * stream_unrolled_fit(g.K, max_rows);
+    if (stream_ok && (max_rows <= 64 || few)) {
         g.row_hi = 0x7fffffff;                 // every expert streams, `fit` rows per block
-        if (stream_unrolled_supports(g.K, bits, smode)) return launch_stream_unrolled(g, bits, max_rows, s);
+        if (unrolled) return launch_stream_unrolled(g, bits, max_rows, s);
         return launch_stream_gemm(g, bits, smode, max_rows, s);
     }
     if (stream_ok && mean <= 96) {

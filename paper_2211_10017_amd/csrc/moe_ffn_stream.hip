@@ -182,8 +182,10 @@ static void launch_stream(const GemmArgs &p, int tpw, dim3 grid, hipStream_t s)
 // loop edge the compiler's wait before block b is "all but the 15 youngest loads", i.e. only the
 // load that block needs.  Every wavefront computes as its data trickles in, and the last wait of
 // the kernel is for a single block.
-constexpr int kStageVecs = 16;         // 16-byte vectors of activation rows one thread stages
-constexpr int kUnrolledFitCap = 16;    // rows per block: 16 rows of K = 1024 leave LDS for three blocks per CU
+constexpr int kStageVecs = 16;         // 16-byte vectors of activation rows one thread stages (at most)
+constexpr int kUnrolledFitCap = 16;    // rows per block: 16 rows of K = 1024 leave LDS for several blocks per CU
+// vectors one thread stages for a K extent: all of kUnrolledFitCap rows, but no more than kStageVecs
+__host__ __device__ constexpr int stage_vecs(int K) { return kUnrolledFitCap * (K / 8) / 256 < kStageVecs ? kUnrolledFitCap * (K / 8) / 256 : kStageVecs; }
 
 //
 // KS = 4 splits the K range of a slab over the four wavefronts of the block (a slab of 64 blocks
@@ -232,8 +234,9 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     const int total = rows * VPR;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 *a_vec = reinterpret_cast<const u32x4 *>(p.a + (size_t)lo * K);
-    u32x4 av[kStageVecs];
-    static_for<0, kStageVecs>([&](auto jc) {
+    constexpr int NA = stage_vecs(K) < 1 ? 1 : stage_vecs(K);
+    u32x4 av[NA];
+    static_for<0, NA>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
     });
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     });
     // vectors past the live rows (clamped reads above) land in a per-thread dump slot behind the rows
     uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? 4 * 16 * 64 * 2 : 0) + threadIdx.x * 8;
-    static_for<0, kStageVecs>([&](auto jc) {
+    static_for<0, NA>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         const int idx = j * 256 + (int)threadIdx.x;
         uint16_t *dst = idx < total ? lds_a + (idx / VPR) * LDR + (idx % VPR) * 8 : dump;
@@ -383,7 +386,8 @@ static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_
 // thread) and 64 KB of LDS hold.
 static int unrolled_fit_rows(int K, int max_rows)
 {
-    int fit = kStageVecs * 256 / (K / 8);
+    const int na = stage_vecs(K) < 1 ? 1 : stage_vecs(K);
+    int fit = na * 256 / (K / 8);
     if (fit > kUnrolledFitCap) fit = kUnrolledFitCap;
     if (fit > max_rows) fit = max_rows;
     return fit < 1 ? 1 : fit;
