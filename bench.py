@@ -124,11 +124,11 @@ def main():
     for i in range(args.steps):
         layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
         layer.gate(x, finished)
-        layer.permute(x)
+        layer.permute(x, finished)
         ev[i][0].record()
-        layer.ffn()
+        layer.ffn(x, finished)
         ev[i][1].record()
-        layer.combine()
+        layer.combine(x, finished)
     torch.cuda.synchronize()
     ffn_ms = np.array([a.elapsed_time(b) for a, b in ev])
     launches_per_ffn = 2                       # fc1 and fc2 are two launches of the same kernel

@@ -149,6 +149,30 @@ int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_
                        size_t workspace_bytes, void *stream);
 
 /*
+ * moe_grouped_ffn_wq with the routing fused into the GEMMs, for batches large enough to run in
+ * the tiled kernel: fc1 fetches row r from x[perm_src[r] / k] (no x_perm copy is needed:
+ * moe_permute may be called with x = x_perm = NULL), and, when expert_scale is given (k = 1
+ * only, one expert per token), fc2 stores expert_scale[t] * y[r] straight into out[t],
+ * t = perm_src[r], which replaces moe_combine.
+ *   x [T,d] fp16 (un-permuted); perm_src [R], expert_offsets [E+1] from moe_permute;
+ *   expert_scale [T] fp32 or NULL; out: [T,d] when expert_scale is given, else y_perm [R,d].
+ *   With pruned rows (Sec. 3.5) and expert_scale given, the rows of pruned tokens in out are
+ *   not written: clear out first, or use moe_combine.
+ * moe_grouped_ffn_wq_routed_supported returns 1 when a call with these sizes is taken (fp16
+ * activations and row counts that run entirely in the tiled kernel); otherwise the call
+ * returns MOE_ERR_UNSUPPORTED and the un-fused sequence has to be used.  Workspace as for
+ * moe_grouped_ffn_wq.
+ */
+int moe_grouped_ffn_wq_routed_supported(int R, int E, int max_rows_per_expert, int d, int F, int bits,
+                                        int group_size, int act_dtype);
+int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_src, int k,
+                              const float *expert_scale, const int32_t *expert_offsets, int R, int E,
+                              int max_rows_per_expert, int d, int F, int bits, int group_size,
+                              const void *w1_packed, const void *s1, const void *b1,
+                              const void *w2_packed, const void *s2, const void *b2, void *out,
+                              int out_dtype, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Table 1 (Sec. 4.1): throughput of one grouped GEMM  y[r] = x_perm[r] @ deq(W[e])  on about 40
  * tokens spread over 1..32 active experts, with fp16, int8 and int4 weights.  This entry runs
  * that single GEMM with the decode-sized streaming kernels of moe_grouped_ffn_wq:

@@ -20,7 +20,8 @@ _DT = {torch.float16: MOE_F16, torch.bfloat16: MOE_BF16, torch.float32: MOE_F32}
 
 EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
            "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
-           "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq"]
+           "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq",
+           "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed"]
 
 _lib = None
 
@@ -54,6 +55,11 @@ def load():
     lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_ffn_wq.restype = i
     lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_grouped_ffn_wq_routed_supported.restype = i
+    lib.moe_grouped_ffn_wq_routed_supported.argtypes = [i, i, i, i, i, i, i, i]
+    lib.moe_grouped_ffn_wq_routed.restype = i
+    lib.moe_grouped_ffn_wq_routed.argtypes = [vp, i, vp, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i,
+                                              vp, sz, vp]
     lib.moe_pack_fp16_experts.restype = i
     lib.moe_pack_fp16_experts.argtypes = [vp, i, i, i, vp, vp]
     lib.moe_grouped_gemm_wq.restype = i
@@ -212,3 +218,29 @@ def moe_grouped_gemm_wq(x_perm, expert_offsets, E: int, K: int, N: int, bits: in
                                     _ptr(y), _DT[y.dtype], _stream())
     _check(rc, "moe_grouped_gemm_wq")
     return y
+
+
+def moe_grouped_ffn_wq_routed_supported(R: int, E: int, max_rows_per_expert: int, d: int, F: int, bits: int,
+                                        group_size: int, act_dtype) -> bool:
+    return bool(load().moe_grouped_ffn_wq_routed_supported(R, E, max_rows_per_expert, d, F, bits, group_size,
+                                                           _DT[act_dtype]))
+
+
+def moe_grouped_ffn_wq_routed(x, perm_src, k: int, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
+                              w1_packed, s1, w2_packed, s2, b1=None, b2=None, expert_scale=None, out=None,
+                              out_dtype=None, workspace=None, max_rows_per_expert: int = 0):
+    """FFN with the gather (and, with expert_scale and k = 1, the combine) fused into the GEMMs."""
+    R = perm_src.shape[0]
+    T = x.shape[0]
+    if out is None:
+        out = torch.empty((T if expert_scale is not None else R, d), dtype=out_dtype or x.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, x.dtype), dtype=torch.uint8, device=x.device)
+    rc = load().moe_grouped_ffn_wq_routed(
+        _ptr(x, torch.float16, "x"), _DT[x.dtype], _ptr(perm_src, torch.int32, "perm_src"), k,
+        _ptr(expert_scale, torch.float32, "expert_scale"), _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E,
+        max_rows_per_expert, d, F, bits, group_size, _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"),
+        _ptr(b1, torch.float16, "b1"), _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"),
+        _ptr(b2, torch.float16, "b2"), _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moe_grouped_ffn_wq_routed")
+    return out

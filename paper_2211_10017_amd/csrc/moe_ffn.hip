@@ -94,12 +94,27 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     return launch_tiled_gemm(g, bits, smode, bf, s);
 }
 
-extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
-                                  int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
-                                  const void *w1_packed,
-                                  const void *s1, const void *b1, const void *w2_packed, const void *s2,
-                                  const void *b2, void *y_perm, int y_dtype, void *workspace,
-                                  size_t workspace_bytes, void *stream)
+// true when a call with these sizes runs both GEMMs in the tiled kernel alone (the only kernel
+// that takes rows through the routing index)
+static bool tiled_only(int R, int E, int max_rows, int d, int F, int bits, bool grouped, bool bf)
+{
+    using namespace moe;
+    const int mean = (R + E - 1) / E;
+    const int smode = grouped ? SCALE_GROUP : SCALE_CHANNEL;
+    for (int K : {d, F}) {
+        const bool stream_ok = !bf && stream_gemm_supports(K, bits, smode);
+        if (stream_ok && (max_rows <= 64 || mean <= 96)) return false;
+    }
+    return true;
+}
+
+static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
+                    int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                    const void *w1_packed,
+                    const void *s1, const void *b1, const void *w2_packed, const void *s2,
+                    const void *b2, void *y_perm, int y_dtype, void *workspace,
+                    size_t workspace_bytes, void *stream,
+                    const int32_t *perm_src, int k, const float *expert_scale)
 {
     using namespace moe;
     if (!expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || (R != 0 && (!x_perm || !y_perm)))
@@ -137,6 +152,7 @@ extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32
     g1.wq = (const uint8_t *)w1_packed; g1.scales = (const __half *)s1; g1.bias = (const __half *)b1;
     g1.out = h; g1.E = E; g1.R = R; g1.K = d; g1.N = F; g1.g = grouped ? group_size : d;
     g1.out_dtype = act_dtype; g1.relu = 1;
+    g1.a_src = perm_src; g1.a_div = k;
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, R, d, pow_x);
         int rc = check_launch("moe_grouped_ffn_wq (row scale x)");
@@ -151,12 +167,57 @@ extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32
     g2.wq = (const uint8_t *)w2_packed; g2.scales = (const __half *)s2; g2.bias = (const __half *)b2;
     g2.out = y_perm; g2.K = F; g2.N = d; g2.g = grouped ? group_size : F;
     g2.out_dtype = y_dtype; g2.relu = 0;
+    g2.a_src = nullptr;
+    if (expert_scale) { g2.out_dst = perm_src; g2.out_scale = expert_scale; }
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)h, R, F, pow_h);
         rc = check_launch("moe_grouped_ffn_wq (row scale h)");
         if (rc) return rc;
     }
     return run_gemm(g2, bits, grouped ? SCALE_GROUP : SCALE_CHANNEL, bf, max_rows, s);
+}
+
+extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
+                                  int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                                  const void *w1_packed,
+                                  const void *s1, const void *b1, const void *w2_packed, const void *s2,
+                                  const void *b2, void *y_perm, int y_dtype, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    return ffn_impl(x_perm, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, w1_packed,
+                    s1, b1, w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, 1, nullptr);
+}
+
+// The same pair of GEMMs with the row gather (and, for k = 1, the un-permute and gate scale) fused
+// into them; built on the tiled kernel only.
+extern "C" int moe_grouped_ffn_wq_routed_supported(int R, int E, int max_rows_per_expert, int d, int F,
+                                                   int bits, int group_size, int act_dtype)
+{
+    using namespace moe;
+    if (R <= 0 || E <= 0 || d <= 0 || F <= 0 || act_dtype != MOE_F16) return 0;
+    const int max_rows = max_rows_per_expert > 0 && max_rows_per_expert < R ? max_rows_per_expert : R;
+    const bool grouped = group_size != 0 && !(group_size == d && group_size == F);
+    return tiled_only(R, E, max_rows, d, F, bits, grouped, false) ? 1 : 0;
+}
+
+extern "C" int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_src, int k,
+                                         const float *expert_scale, const int32_t *expert_offsets, int R,
+                                         int E, int max_rows_per_expert, int d, int F, int bits,
+                                         int group_size, const void *w1_packed, const void *s1,
+                                         const void *b1, const void *w2_packed, const void *s2,
+                                         const void *b2, void *out, int out_dtype, void *workspace,
+                                         size_t workspace_bytes, void *stream)
+{
+    using namespace moe;
+    if (!perm_src) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq_routed: perm_src must not be NULL");
+    if (k < 1 || k > 2) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq_routed: k must be 1 or 2 (k=%d)", k);
+    if (expert_scale && k != 1)
+        return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq_routed: the fused un-permute needs k = 1 (one expert per token)");
+    if (!moe_grouped_ffn_wq_routed_supported(R, E, max_rows_per_expert, d, F, bits, group_size, act_dtype))
+        return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_routed: these sizes run (partly) in the streaming kernels or in bf16, "
+                                         "which take permuted rows only: use moe_permute + moe_grouped_ffn_wq + moe_combine");
+    return ffn_impl(x, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, w1_packed, s1, b1,
+                    w2_packed, s2, b2, out, out_dtype, workspace, workspace_bytes, stream, perm_src, k, expert_scale);
 }
 
 // One grouped GEMM of the decode-sized case, for the comparison of Table 1 (fp16 / int8 / int4

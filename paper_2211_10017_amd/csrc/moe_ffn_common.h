@@ -24,6 +24,11 @@ struct GemmArgs {
     int out_dtype, relu;
     int row_lo;               // tiled kernel: only experts with more than row_lo rows
     int row_hi;               // streaming kernel: only experts with 1..row_hi rows
+    // tiled kernel only: rows fetched / stored through the routing index instead of a permuted copy
+    const int32_t *a_src;     // [R] or null: row r of A is a[a_src[r] / a_div]
+    int a_div;
+    const int32_t *out_dst;   // [R] or null: row r of the result goes to out[out_dst[r]], times out_scale[out_dst[r]]
+    const float *out_scale;
 };
 
 int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);

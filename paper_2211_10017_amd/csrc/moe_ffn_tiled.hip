@@ -21,12 +21,19 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     constexpr int BM = 32 * TM;
     constexpr int NW = BITS == 4 ? 1 : 2;             // 16-byte loads per tile per 64-deep K step
     __shared__ __align__(16) uint16_t lds_a[2][BM * kLdsRow];
+    __shared__ int32_t s_dst[BM];          // fused un-permute: destination row and gate scale of each row of the tile
+    __shared__ float s_scale[BM];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int K = p.K, N = p.N;
     int e, col, row0, rows;
     if (!find_item(p.offsets, p.E, p.R, BM, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
 
+    if (p.out_dst && (int)threadIdx.x < rows) {       // read long before the epilogue; the K loop's barriers publish it
+        const int dst = p.out_dst[row0 + threadIdx.x];
+        s_dst[threadIdx.x] = dst;
+        s_scale[threadIdx.x] = p.out_scale[dst];
+    }
     const int nk = K / 64;
     const int ntile0 = (col * 4 + wave) * kTN;         // first 32-channel tile of this wavefront
     const int ntiles = N / 32;
@@ -42,7 +49,8 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
         const int r = row0 + min(a_row + 32 * m, rows - 1);      // clamped: always a valid row
-        a_ptr[m] = p.a + (size_t)r * K + a_seg;
+        const int rs = p.a_src ? p.a_src[r] / p.a_div : r;       // gather fused into the A loads
+        a_ptr[m] = p.a + (size_t)rs * K + a_seg;
         a_down[m] = ABF16 ? p.row_pow[r].x : 1.0f;
     }
     // B: fragment blocks of tile t are contiguous along K
@@ -233,7 +241,12 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                 if (ABF16) v *= p.row_pow[r].y;
                 v += bias;
                 if (p.relu) v = fmaxf(v, 0.0f);
-                const size_t o = (size_t)r * N + n;
+                int ro = r;
+                if (p.out_dst) {                                 // un-permute and gate scale fused into the store
+                    ro = s_dst[rl];
+                    v *= s_scale[rl];
+                }
+                const size_t o = (size_t)ro * N + n;
                 if (p.out_dtype == MOE_F32) reinterpret_cast<float *>(p.out)[o] = v;
                 else if (p.out_dtype == MOE_BF16) reinterpret_cast<uint16_t *>(p.out)[o] = to_bf16_rne(v);
                 else reinterpret_cast<_Float16 *>(p.out)[o] = (_Float16)v;

@@ -10,7 +10,7 @@ from . import binding as B
 
 class MoEExpertLayer:
     def __init__(self, T, d, F, E, k, bits, group_size=0, act_dtype=torch.float16, renormalize=True,
-                 y_dtype=None, out_dtype=torch.float32, device="cuda:0"):
+                 y_dtype=None, out_dtype=torch.float32, device="cuda:0", fuse_routing=True):
         self.T, self.d, self.F, self.E, self.k = T, d, F, E, k
         self.bits, self.group_size, self.renormalize = bits, group_size, renormalize
         self.act_dtype, self.out_dtype = act_dtype, out_dtype
@@ -42,6 +42,9 @@ class MoEExpertLayer:
         self.ws_ffn = torch.empty(B.moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype),
                                   dtype=torch.uint8, device=dev)
         self._plans = {}
+        # large batches: the row gather (and for k = 1 the un-permute and gate scale) run inside
+        # the GEMMs instead of as copies of their own
+        self.routed = bool(fuse_routing) and B.moe_grouped_ffn_wq_routed_supported(R, E, T, d, F, bits, group_size, act_dtype)
 
     # -- offline: quantise one expert matrix from its fp32 master (which = 1 | 2) ------------
     def load_expert(self, which: int, e: int, w_fp32, q_canon_out=None):
@@ -55,24 +58,28 @@ class MoEExpertLayer:
             setattr(self, name, getattr(other, name))
 
     # -- per call ---------------------------------------------------------------------------
+    # The steps one by one (bench.py times them separately); each runs its entry of the same plan
+    # forward() replays, so the fused and un-fused variants cannot drift apart.
+    def _step(self, name, x, finished=None):
+        for fn, args, what in self._plan(x, finished):
+            if what.startswith(name):
+                rc = fn(*args)
+                if rc != 0:
+                    B._check(rc, what)
+
     def gate(self, x, finished=None):
-        return B.moe_gate_topk(x, self.wg, self.gate_bias, self.k, self.renormalize,
-                               out=(self.expert_idx, self.expert_scale), finished=finished)
+        self._step("moe_gate_topk", x, finished)
+        return self.expert_idx, self.expert_scale
 
-    def permute(self, x):
-        return B.moe_permute(self.expert_idx, x, self.E,
-                             out=(self.x_perm, self.perm_src, self.inv_perm, self.expert_offsets),
-                             workspace=self.ws_permute)
+    def permute(self, x, finished=None):
+        self._step("moe_permute", x, finished)
 
-    def ffn(self):
-        return B.moe_grouped_ffn_wq(self.x_perm, self.expert_offsets, self.E, self.d, self.F, self.bits,
-                                    self.group_size, self.w1_packed, self.s1, self.w2_packed, self.s2,
-                                    self.b1, self.b2, y_perm=self.y_perm, workspace=self.ws_ffn,
-                                    max_rows_per_expert=self.T)
+    def ffn(self, x, finished=None):
+        self._step("moe_grouped_ffn_wq", x, finished)
 
-    def combine(self):
-        return B.moe_combine(self.y_perm, self.inv_perm, self.expert_scale, self.T, self.k, out=self.out,
-                             active_rows=self.expert_offsets[self.E:])
+    def combine(self, x, finished=None):
+        self._step("moe_combine", x, finished)       # nothing to do when fc2 stored the output itself
+        return self.out
 
     def forward(self, x, finished=None):
         """The four per-call entry points back to back.  The argument lists are marshalled once per
@@ -80,6 +87,13 @@ class MoEExpertLayer:
         kernels are shorter than the time Python needs to rebuild them.
         finished: uint8 [T] on the device, nonzero for rows pruned from the batch (their output
         rows are zero and their experts' weights are not read on their account)."""
+        for fn, args, name in self._plan(x, finished):
+            rc = fn(*args)
+            if rc != 0:
+                B._check(rc, name)
+        return self.out
+
+    def _plan(self, x, finished):
         opt = lambda t: 0 if t is None else t.data_ptr()  # noqa: E731
         key = (x.data_ptr(), opt(finished), self.w1_packed.data_ptr(), self.w2_packed.data_ptr(), self.s1.data_ptr(),
                self.s2.data_ptr(), self.wg.data_ptr(), opt(self.gate_bias), opt(self.b1), opt(self.b2),
@@ -89,11 +103,7 @@ class MoEExpertLayer:
             calls = self._plans[key] = self._marshal(x, finished, key[-1])
             if len(self._plans) > 256:
                 self._plans.pop(next(iter(self._plans)))
-        for fn, args, name in calls:
-            rc = fn(*args)
-            if rc != 0:
-                B._check(rc, name)
-        return self.out
+        return calls
 
     def _marshal(self, x, finished, stream):
         import ctypes
@@ -108,16 +118,28 @@ class MoEExpertLayer:
         active = vp(self.expert_offsets.data_ptr() + 4 * self.E)
         dt, ydt, odt = B._DT[self.act_dtype], B._DT[self.y_dtype], B._DT[self.out_dtype]
         st = vp(stream)
-        return [
-            (lib.moe_gate_topk, (p(x), dt, p(self.wg), p(self.gate_bias), p(finished), self.T, self.d, self.E, self.k,
-                                 int(self.renormalize), p(self.expert_idx), p(self.expert_scale), st), "moe_gate_topk"),
-            (lib.moe_permute, (p(self.expert_idx), p(x), dt, self.T, self.k, self.E, self.d, p(self.x_perm),
-                               p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
-                               self.ws_permute.numel(), st), "moe_permute"),
-            (lib.moe_grouped_ffn_wq, (p(self.x_perm), dt, p(self.expert_offsets), self.R, self.E, self.T, self.d,
-                                      self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1), p(self.b1),
-                                      p(self.w2_packed), p(self.s2), p(self.b2), p(self.y_perm), ydt,
-                                      p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq"),
-            (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), active, self.T, self.k, self.d,
-                               p(self.out), odt, st), "moe_combine"),
-        ]
+        gate = (lib.moe_gate_topk, (p(x), dt, p(self.wg), p(self.gate_bias), p(finished), self.T, self.d, self.E, self.k,
+                                    int(self.renormalize), p(self.expert_idx), p(self.expert_scale), st), "moe_gate_topk")
+        combine = (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), active, self.T, self.k,
+                                     self.d, p(self.out), odt, st), "moe_combine")
+        if self.routed:
+            # index only (no x_perm copy); fc1 gathers, and fc2 scatters when there is one expert per
+            # token and no pruned row (a pruned token's output row would stay unwritten)
+            scatter = self.k == 1 and finished is None
+            permute = (lib.moe_permute, (p(self.expert_idx), None, dt, self.T, self.k, self.E, self.d, None,
+                                         p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
+                                         self.ws_permute.numel(), st), "moe_permute")
+            ffn = (lib.moe_grouped_ffn_wq_routed,
+                   (p(x), dt, p(self.perm_src), self.k, p(self.expert_scale) if scatter else None, p(self.expert_offsets),
+                    self.R, self.E, self.T, self.d, self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1),
+                    p(self.b1), p(self.w2_packed), p(self.s2), p(self.b2), p(self.out) if scatter else p(self.y_perm),
+                    odt if scatter else ydt, p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq_routed")
+            return [gate, permute, ffn] if scatter else [gate, permute, ffn, combine]
+        permute = (lib.moe_permute, (p(self.expert_idx), p(x), dt, self.T, self.k, self.E, self.d, p(self.x_perm),
+                                     p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
+                                     self.ws_permute.numel(), st), "moe_permute")
+        ffn = (lib.moe_grouped_ffn_wq, (p(self.x_perm), dt, p(self.expert_offsets), self.R, self.E, self.T, self.d,
+                                        self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1), p(self.b1),
+                                        p(self.w2_packed), p(self.s2), p(self.b2), p(self.y_perm), ydt,
+                                        p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq")
+        return [gate, permute, ffn, combine]

@@ -295,3 +295,52 @@ def test_grouped_gemm_matches_oracle(bits, native, K, N):
     max_abs, rel = error_metrics(y.cpu().numpy(), want)
     _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
     assert max_abs <= MAX_ABS_TOL and rel <= 1e-5          # exact weights on both sides: only the fp32 summation order differs
+
+
+# ------------------------------------------------------------------ routing fused into the GEMMs
+@pytest.mark.parametrize("T,k,E,d,F,bits,g", [(700, 1, 5, 128, 256, 4, 0), (300, 2, 3, 192, 320, 8, 0),
+                                               (1500, 1, 4, 256, 512, 4, 128)])
+def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g):
+    _say(f"routed ffn T={T} k={k} E={E} d={d} F={F} bits={bits} g={g}")
+    rng = np.random.default_rng(T + E + bits)
+    x = rng.standard_normal((T, d)).astype(np.float16).astype(np.float32)
+    wg = (rng.standard_normal((d, E)) * 0.05).astype(np.float16).astype(np.float32)
+    w1 = (rng.standard_normal((E, d, F)) * 0.05).astype(np.float32)
+    w2 = (rng.standard_normal((E, F, d)) * 0.05).astype(np.float32)
+    q1, s1 = oracle.quantize(w1, bits, g)
+    q2, s2 = oracle.quantize(w2, bits, g)
+    res = oracle.moe_layer(x, wg, None, q1, s1, q2, s2, k, g, oracle.F16, y_dtype=oracle.F32)
+    _, ds1, p1 = B.moe_quantize_experts(to_dev(w1, torch.float32), bits, g, want_canon=False)
+    _, ds2, p2 = B.moe_quantize_experts(to_dev(w2, torch.float32), bits, g, want_canon=False)
+    xd = to_dev(x, torch.float16)
+    assert B.moe_grouped_ffn_wq_routed_supported(T * k, E, T, d, F, bits, g, torch.float16)
+    idx, scale = B.moe_gate_topk(xd, to_dev(wg, torch.float16), None, k, True)
+    assert np.array_equal(idx.cpu().numpy(), res["expert_idx"])
+    # index only: no x_perm copy
+    R = T * k
+    ps = torch.empty(R, dtype=torch.int32, device=DEV)
+    ip = torch.empty(R, dtype=torch.int32, device=DEV)
+    of = torch.empty(E + 1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(B.moe_permute_workspace_bytes(T, k, E), dtype=torch.uint8, device=DEV)
+    rc = B.load().moe_permute(idx.data_ptr(), None, 0, T, k, E, d, None, ps.data_ptr(), ip.data_ptr(), of.data_ptr(),
+                              ws.data_ptr(), ws.numel(), None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(ps.cpu().numpy(), res["perm_src"]) and np.array_equal(of.cpu().numpy(), res["expert_offsets"])
+    if k == 1:      # gather and un-permute + scale fused: the call returns the layer output
+        out = B.moe_grouped_ffn_wq_routed(xd, ps, k, of, E, d, F, bits, g, p1, ds1, p2, ds2, expert_scale=scale.view(-1),
+                                          out_dtype=torch.float32)
+    else:           # gather fused; combine as usual
+        y = B.moe_grouped_ffn_wq_routed(xd, ps, k, of, E, d, F, bits, g, p1, ds1, p2, ds2, out_dtype=torch.float32)
+        out = B.moe_combine(y, ip, scale, T, k)
+    torch.cuda.synchronize()
+    max_abs, rel = error_metrics(out.cpu().numpy(), res["out"])
+    _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+def test_routed_ffn_refuses_decode_sizes():
+    _say("routed ffn: decode sizes are refused")
+    assert not B.moe_grouped_ffn_wq_routed_supported(128, 32, 64, 1024, 4096, 4, 0, torch.float16)
+    assert not B.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, torch.bfloat16)
+    assert B.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, torch.float16)
