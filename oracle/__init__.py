@@ -185,7 +185,10 @@ def gather_rows(x, perm_src, k: int) -> np.ndarray:
 
 
 # ------------------------------------------------------------------ FFN / combine
-def expert_ffn(x_rows, w1dq, w2dq, act_dtype: int, b1=None, b2=None, return_h: bool = False):
+RELU, GELU = 0, 1
+
+
+def expert_ffn(x_rows, w1dq, w2dq, act_dtype: int, b1=None, b2=None, return_h: bool = False, activation: int = RELU):
     """One expert: relu(x @ w1dq + b1) rounded to act_dtype, then @ w2dq + b2 (unrounded)."""
     x_rows, w1dq, w2dq = _f32(x_rows), _f32(w1dq), _f32(w2dq)
     m, d = x_rows.shape
@@ -197,7 +200,7 @@ def expert_ffn(x_rows, w1dq, w2dq, act_dtype: int, b1=None, b2=None, return_h: b
     h = np.empty((m, F), dtype=np.float32) if return_h else None
     if m:
         _c().orc_expert_ffn(_p(x_rows), m, d, F, _p(w1dq), None if b1 is None else _p(b1),
-                            _p(w2dq), None if b2 is None else _p(b2), act_dtype,
+                            _p(w2dq), None if b2 is None else _p(b2), act_dtype, int(activation),
                             None if h is None else _p(h), _p(y))
     return (y, h) if return_h else y
 
@@ -212,7 +215,7 @@ def combine(y_perm, inv_perm, scale, T: int, k: int, active_rows=None) -> np.nda
 
 
 def grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size: int, act_dtype: int,
-                b1=None, b2=None, rows=None, return_h: bool = False):
+                b1=None, b2=None, rows=None, return_h: bool = False, activation: int = RELU):
     """Grouped expert FFN over expert-contiguous rows (Sec. 3.3, Fig. 1).
 
     q1 [E,d,F] / q2 [E,F,d] int8 codes with fp16-bit scales; expert e owns rows
@@ -237,7 +240,7 @@ def grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size: int, act_dtype: int
         w2 = dequantize(q2[e:e + 1], s2[e:e + 1], group_size)[0]
         res = expert_ffn(x_perm[sel], w1, w2, act_dtype,
                          None if b1 is None else b1[e], None if b2 is None else b2[e],
-                         return_h=return_h)
+                         return_h=return_h, activation=activation)
         if return_h:
             y[sel], h[sel] = res
         else:
@@ -263,7 +266,8 @@ def grouped_gemm(x_perm, offsets, w_dq):
 
 
 def moe_layer(x, wg, gate_bias, q1, s1, q2, s2, k: int, group_size: int, act_dtype: int,
-              renormalize: bool = True, y_dtype: int = F32, b1=None, b2=None, finished=None):
+              renormalize: bool = True, y_dtype: int = F32, b1=None, b2=None, finished=None,
+              activation: int = RELU):
     """Gate -> permute -> grouped FFN -> combine; returns a dict of every intermediate.
     finished [T]: rows pruned from the batch (Sec. 3.5); their output rows are zero."""
     E = q1.shape[0]
@@ -271,7 +275,7 @@ def moe_layer(x, wg, gate_bias, q1, s1, q2, s2, k: int, group_size: int, act_dty
     idx, scale = gate(x, wg, gate_bias, k, renormalize, finished=finished)
     perm_src, inv_perm, offsets = permute(idx, E)
     x_perm = gather_rows(x, perm_src, k)
-    y_perm = grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size, act_dtype, b1, b2)
+    y_perm = grouped_ffn(x_perm, offsets, q1, s1, q2, s2, group_size, act_dtype, b1, b2, activation=activation)
     y_perm = round_to(y_perm, y_dtype)
     out = combine(y_perm, inv_perm, scale, T, k, active_rows=int(offsets[E]))
     return dict(expert_idx=idx, expert_scale=scale, perm_src=perm_src, inv_perm=inv_perm,

@@ -286,12 +286,15 @@ void orc_gather_rows(const float *x, const int32_t *perm_src, int R, int k, int 
 /* ---------------------------------------------------------------- expert FFN (Sec. 3.3-3.4)
  * One expert, m rows: h = relu(x @ W1dq + b1), stored in the activation dtype (the paper keeps
  * activations in FP16); y = h @ W2dq + b2.  The activation function is not named in the
- * paper; ReLU is the reading taken.  y is returned unrounded (rounding of the stored y, if
+ * paper; ReLU is the reading taken (activation 0).  Activation 1 is GELU in its exact form,
+ * x * Phi(x) = 0.5 x (1 + erf(x / sqrt 2)), offered as the second choice the method allows "without
+ * loss of generality".  y is returned unrounded (rounding of the stored y, if
  * any, is the caller's: see orc_round_array). */
 void orc_expert_ffn(const float *x /*[m,d]*/, int m, int d, int F,
                     const float *w1 /*[d,F]*/, const float *b1 /*[F] or NULL*/,
                     const float *w2 /*[F,d]*/, const float *b2 /*[d] or NULL*/,
-                    int act_dtype, float *h_out /*[m,F] or NULL*/, float *y /*[m,d]*/)
+                    int act_dtype, int activation /*0 relu, 1 gelu*/, float *h_out /*[m,F] or NULL*/,
+                    float *y /*[m,d]*/)
 {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int r = 0; r < m; ++r) {
@@ -305,7 +308,8 @@ void orc_expert_ffn(const float *x /*[m,d]*/, int m, int d, int F,
         }
         for (int n = 0; n < F; ++n) {
             double v = acc[n] + (b1 ? (double)b1[n] : 0.0);
-            h[n] = round_to((float)(v > 0.0 ? v : 0.0), act_dtype);
+            double a = activation == 1 ? 0.5 * v * (1.0 + erf(v * 0.70710678118654752440)) : (v > 0.0 ? v : 0.0);
+            h[n] = round_to((float)a, act_dtype);
             if (h_out) h_out[(size_t)r * F + n] = h[n];
         }
         for (int n = 0; n < d; ++n) acc[n] = 0.0;

@@ -3,13 +3,17 @@
 // up to 32 experts; Sec. 3.3, Sec. 3.4).
 //
 // The job is to pull every active expert's packed weights through the chip once, at HBM
-// speed; the arithmetic is small.  A wavefront owns `tpw` consecutive 32-channel slabs of one
-// expert.  Thanks to the [slab][k-block] order of the packed layout its whole weight stream is
-// one contiguous range, read through a ring of sixteen 16-byte-per-lane loads (16 KB per
-// wavefront always in flight): as soon as a fragment block has been unpacked, its ring slot is
-// refilled with the block 16 ahead.  The few activation rows are the MFMA A operand; each lane
-// reads its 8 consecutive K values directly (they are shared by all wavefronts of the expert
-// and stay in L1/L2), prefetched a few blocks ahead.  No LDS, no barriers.
+// speed; the arithmetic is small.  A wavefront owns whole 32-channel slabs of one expert (or a
+// quarter of the K range of one).  Thanks to the [slab][k-block] order of the packed layout its
+// weight stream is one contiguous range, read with sixteen 16-byte-per-lane loads (16 KB per
+// wavefront) in flight.  The few activation rows of the expert are staged once per block in LDS,
+// for the whole K range, and are the MFMA A operand; the weights go from registers through the
+// magic-number conversion into the B operand and never touch LDS.  Experts with more rows than a
+// block holds take further row groups (grid.z), which stream the same weights again.
+//
+// Two kernels: stream_gemm_kernel (any K that is a multiple of 16 fragment blocks: a loop over
+// runs of 16 blocks) and stream_unrolled_kernel (slabs of at most 64 blocks: straight-line code,
+// ring refilled block by block).
 #include <type_traits>
 
 #include "moe_ffn_common.h"

@@ -151,3 +151,19 @@ def test_grouped_gemm_against_library_matmul():
         want = x[off[e]:off[e + 1]].astype(np.float64) @ w[e].astype(np.float64)
         assert np.allclose(got[off[e]:off[e + 1]], want, rtol=1e-6, atol=1e-6)
     assert np.abs(got).max() > 1.0
+
+
+def test_gelu_against_library_gelu():
+    """The second activation (exact GELU) against torch's CPU implementation in fp64, through a
+    one-expert FFN whose second matrix is the identity, so that y is h itself."""
+    import torch
+    rng = np.random.default_rng(31)
+    m, d = 16, 32
+    x = (rng.standard_normal((m, d)) * 2.0).astype(np.float32)
+    eye = np.eye(d, dtype=np.float32)
+    y, h = oracle.expert_ffn(x, eye, eye, oracle.F32, return_h=True, activation=oracle.GELU)
+    want = torch.nn.functional.gelu(torch.from_numpy(x).double()).numpy()
+    assert np.allclose(h, want, rtol=1e-6, atol=1e-7) and np.allclose(y, want, rtol=1e-6, atol=1e-7)
+    assert (h[x < -1.0] < 0).all() and not np.allclose(h, np.maximum(x, 0.0), atol=1e-3)   # it is not ReLU
+    relu = oracle.expert_ffn(x, eye, eye, oracle.F32, activation=oracle.RELU)
+    assert np.array_equal(relu, np.maximum(x, 0.0))
