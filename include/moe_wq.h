@@ -46,6 +46,9 @@ enum {
 /* element types of activation-like tensors */
 enum { MOE_F16 = 0, MOE_BF16 = 1, MOE_F32 = 2 };
 
+/* activation between the two GEMMs of the expert FFN */
+enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1 };
+
 /* Message for the last error returned on this thread ("" if none). */
 const char *moe_last_error(void);
 
@@ -119,11 +122,13 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
 /*
  * Sec. 3.3 (grouped GEMM, Fig. 1) + Sec. 3.4 (dequantisation fused into the GEMM): for every
  * expert e and each of its rows r,
- *     h[r] = relu(x_perm[r] @ deq(W1[e]) + b1[e])   stored in act_dtype
+ *     h[r] = act(x_perm[r] @ deq(W1[e]) + b1[e])    stored in act_dtype
  *     y[r] = h[r] @ deq(W2[e]) + b2[e]              stored in y_dtype
  * with fp16 MFMA and fp32 accumulation; the packed codes are unpacked and dequantised in
  * registers (never written back to memory).  Experts without rows cost no weight traffic.
  *
+ *   activation: MOE_ACT_RELU (the paper does not name the activation; ReLU is the reading
+ *       taken) or MOE_ACT_GELU (exact form x * Phi(x), a second choice)
  *   x_perm [R,d] act_dtype
  *   expert_offsets [E+1] (device): a monotone partition of the R rows, offsets[0] = 0 and
  *       offsets[E] = R, as moe_permute writes it.  The host cannot check it; the kernels force
@@ -143,7 +148,7 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
 size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E, int act_dtype);
 int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
                        int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
-                       const void *w1_packed,
+                       int activation, const void *w1_packed,
                        const void *s1, const void *b1, const void *w2_packed, const void *s2,
                        const void *b2, void *y_perm, int y_dtype, void *workspace,
                        size_t workspace_bytes, void *stream);
@@ -168,7 +173,7 @@ int moe_grouped_ffn_wq_routed_supported(int R, int E, int max_rows_per_expert, i
 int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_src, int k,
                               const float *expert_scale, const int32_t *expert_offsets, int R, int E,
                               int max_rows_per_expert, int d, int F, int bits, int group_size,
-                              const void *w1_packed, const void *s1, const void *b1,
+                              int activation, const void *w1_packed, const void *s1, const void *b1,
                               const void *w2_packed, const void *s2, const void *b2, void *out,
                               int out_dtype, void *workspace, size_t workspace_bytes, void *stream);
 

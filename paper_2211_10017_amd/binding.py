@@ -24,6 +24,7 @@ EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gat
            "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed"]
 
 _lib = None
+ACTIVATIONS = {"relu": 0, "gelu": 1}     # MOE_ACT_RELU, MOE_ACT_GELU
 
 
 class MoeError(RuntimeError):
@@ -54,11 +55,11 @@ def load():
     lib.moe_grouped_ffn_wq_workspace_bytes.restype = sz
     lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_ffn_wq.restype = i
-    lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
     lib.moe_grouped_ffn_wq_routed_supported.restype = i
     lib.moe_grouped_ffn_wq_routed_supported.argtypes = [i, i, i, i, i, i, i, i]
     lib.moe_grouped_ffn_wq_routed.restype = i
-    lib.moe_grouped_ffn_wq_routed.argtypes = [vp, i, vp, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i,
+    lib.moe_grouped_ffn_wq_routed.argtypes = [vp, i, vp, i, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i,
                                               vp, sz, vp]
     lib.moe_pack_fp16_experts.restype = i
     lib.moe_pack_fp16_experts.argtypes = [vp, i, i, i, vp, vp]
@@ -165,7 +166,7 @@ def moe_grouped_ffn_wq_workspace_bytes(R: int, d: int, F: int, E: int, act_dtype
 
 def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
                        w1_packed, s1, w2_packed, s2, b1=None, b2=None, y_dtype=None, y_perm=None,
-                       workspace=None, max_rows_per_expert: int = 0):
+                       workspace=None, max_rows_per_expert: int = 0, activation: str = "relu"):
     R = x_perm.shape[0]
     y_dtype = y_dtype or x_perm.dtype
     if y_perm is None:
@@ -176,6 +177,7 @@ def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int
     rc = load().moe_grouped_ffn_wq(
         _ptr(x_perm, (torch.float16, torch.bfloat16), "x_perm"), _DT[x_perm.dtype],
         _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E, max_rows_per_expert, d, F, bits, group_size,
+        ACTIVATIONS[activation],
         _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"), _ptr(b1, torch.float16, "b1"),
         _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"), _ptr(b2, torch.float16, "b2"),
         _ptr(y_perm), _DT[y_perm.dtype], _ptr(workspace), workspace.numel(), _stream())
@@ -228,7 +230,7 @@ def moe_grouped_ffn_wq_routed_supported(R: int, E: int, max_rows_per_expert: int
 
 def moe_grouped_ffn_wq_routed(x, perm_src, k: int, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
                               w1_packed, s1, w2_packed, s2, b1=None, b2=None, expert_scale=None, out=None,
-                              out_dtype=None, workspace=None, max_rows_per_expert: int = 0):
+                              out_dtype=None, workspace=None, max_rows_per_expert: int = 0, activation: str = "relu"):
     """FFN with the gather (and, with expert_scale and k = 1, the combine) fused into the GEMMs."""
     R = perm_src.shape[0]
     T = x.shape[0]
@@ -239,7 +241,8 @@ def moe_grouped_ffn_wq_routed(x, perm_src, k: int, expert_offsets, E: int, d: in
     rc = load().moe_grouped_ffn_wq_routed(
         _ptr(x, torch.float16, "x"), _DT[x.dtype], _ptr(perm_src, torch.int32, "perm_src"), k,
         _ptr(expert_scale, torch.float32, "expert_scale"), _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E,
-        max_rows_per_expert, d, F, bits, group_size, _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"),
+        max_rows_per_expert, d, F, bits, group_size, ACTIVATIONS[activation], _ptr(w1_packed, torch.uint8, "w1_packed"),
+        _ptr(s1, torch.float16, "s1"),
         _ptr(b1, torch.float16, "b1"), _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"),
         _ptr(b2, torch.float16, "b2"), _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moe_grouped_ffn_wq_routed")

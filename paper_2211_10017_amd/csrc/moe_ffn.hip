@@ -109,7 +109,7 @@ static bool tiled_only(int R, int E, int max_rows, int d, int F, int bits, bool 
 }
 
 static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
-                    int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                    int E, int max_rows_per_expert, int d, int F, int bits, int group_size, int activation,
                     const void *w1_packed,
                     const void *s1, const void *b1, const void *w2_packed, const void *s2,
                     const void *b2, void *y_perm, int y_dtype, void *workspace,
@@ -123,6 +123,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
         return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: R >= 0, max_rows_per_expert >= 0 and E, d, F > 0 required");
     if (d % 64 || F % 64) return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: d and F must be multiples of 64 (d=%d F=%d)", d, F);
     if (bits != 4 && bits != 8) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: bits must be 4 or 8 (got %d)", bits);
+    if (activation != MOE_ACT_RELU && activation != MOE_ACT_GELU) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: unknown activation %d", activation);
     if (act_dtype != MOE_F16 && act_dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: act_dtype must be fp16 or bf16");
     if (y_dtype != MOE_F16 && y_dtype != MOE_BF16 && y_dtype != MOE_F32) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: unknown y_dtype %d", y_dtype);
     if (group_size < 0 || (group_size && (group_size % 64 || d % group_size || F % group_size)))
@@ -151,7 +152,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     g1.a = (const uint16_t *)x_perm; g1.row_pow = pow_x; g1.offsets = expert_offsets;
     g1.wq = (const uint8_t *)w1_packed; g1.scales = (const __half *)s1; g1.bias = (const __half *)b1;
     g1.out = h; g1.E = E; g1.R = R; g1.K = d; g1.N = F; g1.g = grouped ? group_size : d;
-    g1.out_dtype = act_dtype; g1.relu = 1;
+    g1.out_dtype = act_dtype; g1.act = activation;
     g1.a_src = perm_src; g1.a_div = k;
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, R, d, pow_x);
@@ -166,7 +167,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     g2.a = (const uint16_t *)h; g2.row_pow = pow_h;
     g2.wq = (const uint8_t *)w2_packed; g2.scales = (const __half *)s2; g2.bias = (const __half *)b2;
     g2.out = y_perm; g2.K = F; g2.N = d; g2.g = grouped ? group_size : F;
-    g2.out_dtype = y_dtype; g2.relu = 0;
+    g2.out_dtype = y_dtype; g2.act = MOE_ACT_NONE;
     g2.a_src = nullptr;
     if (expert_scale) { g2.out_dst = perm_src; g2.out_scale = expert_scale; }
     if (bf) {
@@ -179,12 +180,12 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
 
 extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
                                   int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
-                                  const void *w1_packed,
+                                  int activation, const void *w1_packed,
                                   const void *s1, const void *b1, const void *w2_packed, const void *s2,
                                   const void *b2, void *y_perm, int y_dtype, void *workspace,
                                   size_t workspace_bytes, void *stream)
 {
-    return ffn_impl(x_perm, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, w1_packed,
+    return ffn_impl(x_perm, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, activation, w1_packed,
                     s1, b1, w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, 1, nullptr);
 }
 
@@ -203,7 +204,7 @@ extern "C" int moe_grouped_ffn_wq_routed_supported(int R, int E, int max_rows_pe
 extern "C" int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_src, int k,
                                          const float *expert_scale, const int32_t *expert_offsets, int R,
                                          int E, int max_rows_per_expert, int d, int F, int bits,
-                                         int group_size, const void *w1_packed, const void *s1,
+                                         int group_size, int activation, const void *w1_packed, const void *s1,
                                          const void *b1, const void *w2_packed, const void *s2,
                                          const void *b2, void *out, int out_dtype, void *workspace,
                                          size_t workspace_bytes, void *stream)
@@ -216,7 +217,7 @@ extern "C" int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int
     if (!moe_grouped_ffn_wq_routed_supported(R, E, max_rows_per_expert, d, F, bits, group_size, act_dtype))
         return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_routed: these sizes run (partly) in the streaming kernels or in bf16, "
                                          "which take permuted rows only: use moe_permute + moe_grouped_ffn_wq + moe_combine");
-    return ffn_impl(x, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, w1_packed, s1, b1,
+    return ffn_impl(x, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, activation, w1_packed, s1, b1,
                     w2_packed, s2, b2, out, out_dtype, workspace, workspace_bytes, stream, perm_src, k, expert_scale);
 }
 
@@ -247,7 +248,7 @@ extern "C" int moe_grouped_gemm_wq(const void *x_perm, const int32_t *expert_off
     GemmArgs g{};
     g.a = (const uint16_t *)x_perm; g.offsets = expert_offsets; g.wq = (const uint8_t *)w_packed;
     g.scales = (const __half *)scales; g.bias = nullptr; g.out = y; g.E = E; g.R = R; g.K = K; g.N = N; g.g = K;
-    g.out_dtype = y_dtype; g.relu = 0; g.row_lo = 0; g.row_hi = 0x7fffffff;
+    g.out_dtype = y_dtype; g.act = MOE_ACT_NONE; g.row_lo = 0; g.row_hi = 0x7fffffff;
     hipStream_t s = as_stream(stream);
     if (bits == 16 || native_convert) return launch_stream_unrolled_variant(g, bits, native_convert != 0, max_rows, s);
     return launch_stream_unrolled(g, bits, max_rows, s);

@@ -21,7 +21,8 @@ struct GemmArgs {
     const __half *bias;       // [E, N] or null
     void *out;                // [R, N]
     int E, R, K, N, g;
-    int out_dtype, relu;
+    int out_dtype;
+    int act;                  // MOE_ACT_NONE (plain GEMM) | MOE_ACT_RELU | MOE_ACT_GELU applied after the bias
     int row_lo;               // tiled kernel: only experts with more than row_lo rows
     int row_hi;               // streaming kernel: only experts with 1..row_hi rows
     // tiled kernel only: rows fetched / stored through the routing index instead of a permuted copy
@@ -39,6 +40,16 @@ bool stream_unrolled_supports(int K, int bits, int smode);
 int stream_unrolled_fit(int K, int max_rows);
 int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s);
 int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s);
+
+enum { MOE_ACT_NONE = -1 };
+
+// The activation between the two GEMMs.  GELU in its exact form x * Phi(x).
+__device__ inline float activate(float v, int act)
+{
+    if (act == MOE_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == MOE_ACT_GELU) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    return v;
+}
 
 __device__ inline uint32_t h2_bits(half2_t v) { return __builtin_bit_cast(uint32_t, v); }
 __device__ inline half2_t bits_h2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
         for (int q = 0; q < 16; ++q) {
             const int rl = rbase + 8 * (q >> 2) + (q & 3);
             float v = acc[q] * cs[sl] + bias[sl];
-            if (p.relu) v = fmaxf(v, 0.0f);
+            v = activate(v, p.act);
             acc[q] = 0.0f;
             if (rl < rows) {
                 if (p.out_dtype == MOE_F16) reinterpret_cast<_Float16 *>(out_rows)[o] = (_Float16)v;
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
                     v[q] = acc[q] * cs[sl] + bias[sl];
-                    if (p.relu) v[q] = fmaxf(v[q], 0.0f);
+                    v[q] = activate(v[q], p.act);
                     acc[q] = 0.0f;
                 }
                 auto put = [&](auto *out) {             // rows rbase+0..3, +8..11, +16..19, +24..27
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
                     const float *src = part + ((wave * 4 + i) * 64 + lane);
                     v[i] = ((src[0] + src[16 * 64]) + src[2 * 16 * 64]) + src[3 * 16 * 64];
                     v[i] = v[i] * cs[sl] + bias[sl];
-                    if (p.relu) v[i] = fmaxf(v[i], 0.0f);
+                    v[i] = activate(v[i], p.act);
                 }
                 auto put = [&](auto *out) {
                     size_t o = (size_t)(rbase + 8 * wave) * N + n;

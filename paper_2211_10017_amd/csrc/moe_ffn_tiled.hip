@@ -240,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                 float v = acc[m][t][i] * cs;
                 if (ABF16) v *= p.row_pow[r].y;
                 v += bias;
-                if (p.relu) v = fmaxf(v, 0.0f);
+                v = activate(v, p.act);
                 int ro = r;
                 if (p.out_dst) {                                 // un-permute and gate scale fused into the store
                     ro = s_dst[rl];

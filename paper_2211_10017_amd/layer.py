@@ -10,10 +10,11 @@ from . import binding as B
 
 class MoEExpertLayer:
     def __init__(self, T, d, F, E, k, bits, group_size=0, act_dtype=torch.float16, renormalize=True,
-                 y_dtype=None, out_dtype=torch.float32, device="cuda:0", fuse_routing=True):
+                 y_dtype=None, out_dtype=torch.float32, device="cuda:0", fuse_routing=True, activation="relu"):
         self.T, self.d, self.F, self.E, self.k = T, d, F, E, k
         self.bits, self.group_size, self.renormalize = bits, group_size, renormalize
         self.act_dtype, self.out_dtype = act_dtype, out_dtype
+        self.activation = B.ACTIVATIONS[activation]
         # y_perm is kept in fp32 for bf16 activations: an 8-bit significand on y would cost
         # more than the layer's whole error budget
         self.y_dtype = y_dtype or (torch.float32 if act_dtype == torch.bfloat16 else act_dtype)
@@ -131,7 +132,7 @@ class MoEExpertLayer:
                                          self.ws_permute.numel(), st), "moe_permute")
             ffn = (lib.moe_grouped_ffn_wq_routed,
                    (p(x), dt, p(self.perm_src), self.k, p(self.expert_scale) if scatter else None, p(self.expert_offsets),
-                    self.R, self.E, self.T, self.d, self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1),
+                    self.R, self.E, self.T, self.d, self.F, self.bits, self.group_size, self.activation, p(self.w1_packed), p(self.s1),
                     p(self.b1), p(self.w2_packed), p(self.s2), p(self.b2), p(self.out) if scatter else p(self.y_perm),
                     odt if scatter else ydt, p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq_routed")
             return [gate, permute, ffn] if scatter else [gate, permute, ffn, combine]
@@ -139,7 +140,7 @@ class MoEExpertLayer:
                                      p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_permute),
                                      self.ws_permute.numel(), st), "moe_permute")
         ffn = (lib.moe_grouped_ffn_wq, (p(self.x_perm), dt, p(self.expert_offsets), self.R, self.E, self.T, self.d,
-                                        self.F, self.bits, self.group_size, p(self.w1_packed), p(self.s1), p(self.b1),
+                                        self.F, self.bits, self.group_size, self.activation, p(self.w1_packed), p(self.s1), p(self.b1),
                                         p(self.w2_packed), p(self.s2), p(self.b2), p(self.y_perm), ydt,
                                         p(self.ws_ffn), self.ws_ffn.numel(), st), "moe_grouped_ffn_wq")
         return [gate, permute, ffn, combine]

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.moe_abi_version() == 2
+    assert lib.moe_abi_version() == 3
 
 
 def test_workspace_queries_are_host_functions(lib):
@@ -51,11 +51,13 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.moe_gate_topk(fake, 0, fake, None, None, 4, 64, 300, 1, 1, fake, fake, None) == 2    # E too large
     assert lib.moe_permute(fake, fake, 0, 4, 1, 8, 60, fake, fake, fake, fake, None, 0, None) == 1   # row not 16 B
     assert lib.moe_permute(fake, fake, 0, 8192, 1, 8, 64, fake, fake, fake, fake, None, 0, None) == 3  # no workspace
-    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 0, 96, 128, 4, 0, fake, fake, None, fake, fake, None,
+    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 0, 96, 128, 4, 0, 0, fake, fake, None, fake, fake, None,
                                   fake, 0, fake, 1 << 20, None) == 1                           # d % 64
-    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 0, 64, 128, 4, 0, fake, fake, None, fake, fake, None,
+    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 0, 64, 128, 4, 0, 0, fake, fake, None, fake, fake, None,
                                   fake, 0, fake, 16, None) == 3                                # workspace too small
     assert b"workspace" in lib.moe_last_error()
+    assert lib.moe_grouped_ffn_wq(fake, 0, fake, 8, 2, 0, 64, 128, 4, 0, 7, fake, fake, None, fake, fake, None,
+                                  fake, 0, fake, 1 << 20, None) == 2                           # unknown activation
     assert lib.moe_combine(fake, 0, fake, fake, None, 4, 1, 60, fake, 2, None) == 1
     assert lib.moe_combine(fake, 5, fake, fake, None, 4, 1, 64, fake, 2, None) == 2
 

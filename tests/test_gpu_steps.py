@@ -108,7 +108,7 @@ def test_permute_no_tokens():
 
 
 # ------------------------------------------------------------------ grouped FFN
-def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False):
+def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, activation="relu"):
     rng = np.random.default_rng(seed)
     E = len(rows_per_expert)
     off = np.concatenate([[0], np.cumsum(rows_per_expert)]).astype(np.int32)
@@ -127,9 +127,11 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False):
         ob1 = rng.standard_normal((E, F)).astype(np.float16).astype(np.float32) * 0.1
         ob2 = rng.standard_normal((E, d)).astype(np.float16).astype(np.float32) * 0.1
         b1, b2 = to_dev(ob1, torch.float16), to_dev(ob2, torch.float16)
-    y = B.moe_grouped_ffn_wq(x, to_dev(off, torch.int32), E, d, F, bits, g, p1, s1, p2, s2, b1, b2, y_dtype=y_dt)
+    y = B.moe_grouped_ffn_wq(x, to_dev(off, torch.int32), E, d, F, bits, g, p1, s1, p2, s2, b1, b2, y_dtype=y_dt,
+                             activation=activation)
     torch.cuda.synchronize()
-    want = oracle.grouped_ffn(x.float().cpu().numpy(), off, q1, os1, q2, os2, g, oracle_dtype_code(tdt), ob1, ob2)
+    want = oracle.grouped_ffn(x.float().cpu().numpy(), off, q1, os1, q2, os2, g, oracle_dtype_code(tdt), ob1, ob2,
+                              activation=B.ACTIVATIONS[activation])
     want = oracle.round_to(want, oracle_dtype_code(y_dt))
     return y.float().cpu().numpy(), want
 
@@ -172,6 +174,19 @@ def test_grouped_ffn_biases_few_rows():
     got, want = _ffn_case([5, 9], 1024, 4096, 4, 0, "f16", torch.float32, seed=6, with_bias=True)
     max_abs, rel = error_metrics(got, want)
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("rows,d,F,bits,g", [([5, 9], 1024, 4096, 4, 0),          # straight-line streaming kernels
+                                              ([7, 0, 16], 512, 8192, 8, 0),       # run-loop streaming kernel (fc2)
+                                              ([100, 260, 7], 256, 512, 4, 128)])  # tiled kernel, group scales
+def test_grouped_ffn_gelu(rows, d, F, bits, g):
+    _say(f"ffn with GELU rows={rows} d={d} F={F} bits={bits} g={g}")
+    got, want = _ffn_case(rows, d, F, bits, g, "f16", torch.float32, seed=9, with_bias=True, activation="gelu")
+    relu, _ = _ffn_case(rows, d, F, bits, g, "f16", torch.float32, seed=9, with_bias=True, activation="relu")
+    max_abs, rel = error_metrics(got, want)
+    _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+    assert error_metrics(relu, want)[1] > 0.02                  # and it is not ReLU
 
 
 def test_grouped_ffn_no_rows():
