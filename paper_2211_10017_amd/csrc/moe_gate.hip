@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
                                                    float *__restrict__ expert_scale)
 {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: addresses built from it are scalar
     const int G = 64 / EL;                        // token groups per wavefront
     const int grp = lane / EL, le = lane % EL;
     const int ntok = G * TB;                 // tokens per block
@@ -52,10 +53,11 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 
     // wave-private staging areas: x [ntok][128] and (NE == 1) the gate weight block [128][E]
     constexpr bool WLDS = NE == 1;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (WLDS ? (size_t)kGateWRow * kGateBlk : 0);
+    const size_t x_halfs = (GM == 1 && NE == 1) ? 0 : (size_t)ntok * kGateBlk;   // (x through scalar loads: no staging)
+    const size_t wave_halfs = x_halfs + (WLDS ? (size_t)kGateWRow * kGateBlk : 0);
     uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * wave_halfs;
-    uint16_t *ws = xs + (size_t)ntok * kGateBlk;
-    float *part = reinterpret_cast<float *>(smem + (size_t)4 * wave_halfs * 2);  // [4][NE][TB][64]
+    uint16_t *ws = xs + x_halfs;
+    float *part = reinterpret_cast<float *>(smem);   // [4][NE][TB][64], over the staging areas once they are used up
 
     float acc[NE][TB];
 #pragma unroll
@@ -67,7 +69,11 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     const int nblk = (d + kGateBlk - 1) / kGateBlk;
     const int turns = (nblk + 3) / 4;             // same trip count for all four wavefronts
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    constexpr int XR = GM * TB >= 4 ? GM * TB / 4 : 1;   // x vectors per lane per turn (ntok <= GM * TB rows, 4 rows per pass)
+    // GM == 1 and at most 64 experts (a lane group is the whole wavefront): a token's features are
+    // the same for every lane, so they are fetched with scalar loads and feed the MACs from scalar
+    // registers; no x staging.  (With more experts per lane the scalar registers run out.)
+    constexpr bool SX = GM == 1 && NE == 1;
+    constexpr int XR = SX ? 1 : (GM * TB >= 4 ? GM * TB / 4 : 1);   // x vectors per lane per turn (ntok <= GM * TB rows, 4 rows per pass)
     constexpr int WR = WLDS ? 16 : 1;             // gate-weight vectors per lane per turn (128 x E halfs, E <= 64)
     struct Staged { u32x4 x[XR]; u32x4 w[WR]; };
 
@@ -77,7 +83,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
         const int i0 = blk * kGateBlk;
         const int lim = min(kGateBlk, d - i0);
 #pragma unroll
-        for (int r = 0; r < XR; ++r) {
+        for (int r = 0; r < (SX ? 0 : XR); ++r) {
             const int row = (lane >> 4) + 4 * r;
             const int seg = (lane & 15) * 8;
             const int t = min(t0 + min(row, ntok - 1), T - 1);
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
         const int blk = turn * 4 + wave;
         const int lim = blk < nblk ? min(kGateBlk, d - blk * kGateBlk) : 0;     // multiple of 8
 #pragma unroll
-        for (int r = 0; r < XR; ++r) {
+        for (int r = 0; r < (SX ? 0 : XR); ++r) {
             const int row = (lane >> 4) + 4 * r;
             const int seg = (lane & 15) * 8;
             if (row < ntok) {
@@ -133,7 +139,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             }
         }
     };
-    auto compute = [&](int turn) {
+    auto compute = [&](int turn) __attribute__((always_inline)) {
         const int blk = turn * 4 + wave;
         const int i0 = blk * kGateBlk;
         const int lim = blk < nblk ? min(kGateBlk, d - i0) : 0;
@@ -154,8 +160,12 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             for (int b0 = 0; b0 < TB; b0 += XB) {
                 uint4 raw[XB];
 #pragma unroll
-                for (int b = 0; b < XB; ++b)
-                    raw[b] = *reinterpret_cast<const uint4 *>(xs + (grp * TB + b0 + b) * kGateBlk + i);
+                for (int b = 0; b < XB; ++b) {
+                    if (SX)     // uniform address: a scalar load
+                        raw[b] = *reinterpret_cast<const uint4 *>(x + (size_t)min(t0 + b0 + b, T - 1) * d + i0 + i);
+                    else
+                        raw[b] = *reinterpret_cast<const uint4 *>(xs + (grp * TB + b0 + b) * kGateBlk + i);
+                }
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
 #pragma unroll
@@ -187,6 +197,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
         }
     }
 
+    __syncthreads();                              // every wavefront is done with its staging area
 #pragma unroll
     for (int a = 0; a < NE; ++a)
 #pragma unroll
@@ -285,8 +296,9 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     // most of the chip idle
     const int tb = (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
-    const size_t wave_halfs = (size_t)ntok * kGateBlk + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
-    const size_t smem = (size_t)4 * wave_halfs * 2 + (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;
+    const size_t wave_halfs = (tb == 16 && NE == 1 ? 0 : (size_t)ntok * kGateBlk) + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
+    const size_t part_bytes = (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;      // shares the staging space
+    const size_t smem = (size_t)4 * wave_halfs * 2 > part_bytes ? (size_t)4 * wave_halfs * 2 : part_bytes;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
     hipStream_t s = as_stream(stream);
