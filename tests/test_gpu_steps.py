@@ -359,3 +359,55 @@ def test_routed_ffn_refuses_decode_sizes():
     assert not B.moe_grouped_ffn_wq_routed_supported(128, 32, 64, 1024, 4096, 4, 0, torch.float16)
     assert not B.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, torch.bfloat16)
     assert B.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, torch.float16)
+
+
+# ------------------------------------------------------------------ limits and degenerate shapes
+@pytest.mark.parametrize("T,d,E,k", [(3, 64, 256, 2), (5, 8, 2, 2), (1, 4096, 64, 1), (70, 72, 5, 1)])
+def test_gate_limits(T, d, E, k):
+    _say(f"gate limits T={T} d={d} E={E} k={k}")
+    rng = np.random.default_rng(T * 7 + E)
+    x = to_dev(rng.standard_normal((T, d)).astype(np.float32), torch.float16)
+    wg = to_dev((rng.standard_normal((d, E)) * 0.1).astype(np.float32), torch.float16)
+    oi, osc = oracle.gate(x.float().cpu().numpy(), wg.float().cpu().numpy(), None, k, True)
+    gi, gs = B.moe_gate_topk(x, wg, None, k, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    assert np.allclose(gs.cpu().numpy(), osc, rtol=1e-5, atol=1e-9)
+
+
+def test_permute_most_experts():
+    _say("permute E=1024")
+    rng = np.random.default_rng(77)
+    T, k, E, d = 3000, 2, 1024, 64
+    idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    x = rng.standard_normal((T, d)).astype(np.float16)
+    perm_src, inv_perm, off = oracle.permute(idx, E)
+    xp, ps, ip, of = B.moe_permute(to_dev(idx, torch.int32), to_dev(x, torch.float16), E)
+    torch.cuda.synchronize()
+    assert np.array_equal(of.cpu().numpy(), off) and np.array_equal(ps.cpu().numpy(), perm_src)
+    assert np.array_equal(ip.cpu().numpy(), inv_perm) and np.array_equal(xp.cpu().numpy(), x[perm_src // k])
+
+
+@pytest.mark.parametrize("rows,d,F,bits,g", [([1], 64, 64, 4, 0), ([1], 64, 64, 8, 64), ([0, 0, 2], 64, 128, 8, 0),
+                                              ([128, 32, 64], 64, 64, 4, 0)])
+def test_grouped_ffn_smallest_shapes(rows, d, F, bits, g):
+    _say(f"ffn smallest shapes rows={rows} d={d} F={F} bits={bits} g={g}")
+    got, want = _ffn_case(rows, d, F, bits, g, "f16", torch.float32, seed=3)
+    max_abs, rel = error_metrics(got, want)
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+def test_quantize_smallest_shape_and_extremes():
+    _say("quantize K=64 N=32, huge and tiny weights")
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((2, 64, 32)).astype(np.float32)
+    w[0, :, 0] *= 1e4                                            # scale near the top of fp16
+    w[0, :, 1] *= 1e-7                                           # scale in the fp16 subnormals
+    w[1, :, 2] = 0.0
+    for bits in (4, 8):
+        q, s, p = B.moe_quantize_experts(to_dev(w, torch.float32), bits, 0)
+        torch.cuda.synchronize()
+        oq, os_ = oracle.quantize(w, bits, 0)
+        want_q = oq if bits == 8 else oracle.pack_int4(oq)
+        assert np.array_equal(q.cpu().numpy(), want_q)
+        assert np.array_equal(s.cpu().numpy().view(np.uint16), os_)
