@@ -159,7 +159,9 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
         int rc = check_launch("moe_grouped_ffn_wq (row scale x)");
         if (rc) return rc;
     }
-    int rc = run_gemm(g1, bits, grouped ? (bf ? SCALE_GROUP_SPLIT : SCALE_GROUP) : SCALE_CHANNEL, bf, max_rows, s);
+    // (groups of 128: exact codes, group sums folded in fp32; other group sizes: the two-term form)
+    const int smode1 = !grouped ? SCALE_CHANNEL : !bf ? SCALE_GROUP : group_size == 128 ? SCALE_GROUP_ACC : SCALE_GROUP_SPLIT;
+    int rc = run_gemm(g1, bits, smode1, bf, max_rows, s);
     if (rc) return rc;
 
     // fc2: y = h @ deq(W2) + b2

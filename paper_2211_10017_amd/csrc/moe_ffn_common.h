@@ -10,7 +10,7 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-enum { SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_GROUP_SPLIT = 2 };
+enum { SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_GROUP_SPLIT = 2, SCALE_GROUP_ACC = 3 };
 
 struct GemmArgs {
     const uint16_t *a;        // [R, K] fp16 or bf16 bit patterns

@@ -77,6 +77,14 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.0f;
 
+    // SCALE_GROUP_ACC (groups of 128 = the two K steps of one loop trip): the codes enter the MFMAs
+    // unscaled (exact), a group's products are summed in accg and folded into acc with the group's
+    // scale in fp32.  Exact like the two-term form, at half its MFMA count; needs the registers of a
+    // second accumulator set, so it is built for row tiles of at most 64 rows.
+    constexpr bool ACC = SMODE == SCALE_GROUP_ACC;
+    static_assert(!ACC || TM <= 2, "two accumulator sets fit for TM <= 2 only");
+    float16_t accg[ACC ? TM : 1][kTN];
+
     // Activations are fetched one K step ahead (they come from L2); packed weights and group
     // scales two steps ahead, into two register sets used alternately (they come from HBM, and
     // one step of MFMA work is shorter than that latency).
@@ -197,11 +205,30 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                         stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
 #pragma unroll
                     for (int t = 0; t < kTN; ++t) {
-                        acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), acc[m][t], 0, 0, 0);
-                        if (SMODE == SCALE_GROUP_SPLIT)
-                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[j & JM][t]), acc[m][t], 0, 0, 0);
+                        if constexpr (ACC) {
+                            float16_t c = accg[m][t];
+                            if (SL == 0 && j == 0)          // first products of a group: start from zero
+#pragma unroll
+                                for (int i = 0; i < 16; ++i) c[i] = 0.0f;
+                            accg[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), c, 0, 0, 0);
+                        } else {
+                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), acc[m][t], 0, 0, 0);
+                            if (SMODE == SCALE_GROUP_SPLIT)
+                                acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[j & JM][t]), acc[m][t], 0, 0, 0);
+                        }
                     }
                 }
+            }
+        }
+        if constexpr (ACC && SL == 1) {                 // end of the group: acc += scale * accg
+#pragma unroll
+            for (int t = 0; t < kTN; ++t) {
+                const float sf = (float)sc[t];
+#pragma unroll
+                for (int m = 0; m < TM; ++m)
+                    if (m < LIVE)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[m][t][i] = fmaf(accg[m][t][i], sf, acc[m][t][i]);
             }
         }
     };
@@ -272,6 +299,9 @@ static void launch_mode(const GemmArgs &p, int smode, bool abf16, int tm, dim3 g
     } else if (smode == SCALE_GROUP) {
         if (abf16) launch_tm<BITS, SCALE_GROUP, true>(p, tm, grid, s);
         else launch_tm<BITS, SCALE_GROUP, false>(p, tm, grid, s);
+    } else if (smode == SCALE_GROUP_ACC) {                 // bf16 rows only, row tiles of at most 64 rows
+        if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, true, 1>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, true, 2>), grid, dim3(256), 0, s, p);
     } else {
         if (abf16) launch_tm<BITS, SCALE_GROUP_SPLIT, true>(p, tm, grid, s);
         else launch_tm<BITS, SCALE_GROUP_SPLIT, false>(p, tm, grid, s);
@@ -282,7 +312,8 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
 {
     // row-tile height from the mean rows per expert (the offsets themselves stay on the device)
     const int mean = (p.R + p.E - 1) / p.E;
-    const int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
+    int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
+    if (smode == SCALE_GROUP_ACC && tm > 2) tm = 2;
     const int bm = 32 * tm;
     const long most = (long)p.R / (p.row_lo + 1);               // experts that can exceed row_lo rows
     const long slots = (long)p.R / bm + (p.E < most ? p.E : most);
