@@ -214,10 +214,15 @@ __device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, i
             const int local = (int)(item - (long)(base + excl) * ncol);
             const int c = local / t_e, mt = local % t_e;
             const int lo_s = __shfl(lo, src), hi_s = __shfl(hi, src);
+            // The expert's rows, in units of 32 (one MFMA row tile), are dealt evenly to its t_e
+            // tiles: 270 rows become 96 + 96 + 78 rather than 128 + 128 + 14, the same matrix
+            // work without a nearly empty tile that streams a whole weight block for 14 rows.
+            const int units = (hi_s - lo_s + 31) / 32, per = units / t_e, extra = units % t_e;
+            const int first = lo_s + 32 * (mt * per + min(mt, extra));
             *e_out = e0 + src;
             *col = c;
-            *row0 = lo_s + mt * BM;
-            *rows = min(BM, hi_s - (lo_s + mt * BM));
+            *row0 = first;
+            *rows = min(32 * (per + (mt < extra ? 1 : 0)), hi_s - first);
             return true;
         }
         base += __shfl(incl, 63);

@@ -24,10 +24,12 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     __shared__ int32_t s_dst[BM];          // fused un-permute: destination row and gate scale of each row of the tile
     __shared__ float s_scale[BM];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: tile addresses stay scalar
     const int K = p.K, N = p.N;
     int e, col, row0, rows;
     if (!find_item(p.offsets, p.E, p.R, BM, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
+    e = __builtin_amdgcn_readfirstlane(e), col = __builtin_amdgcn_readfirstlane(col);      // the same in every lane: kept in scalar registers
+    row0 = __builtin_amdgcn_readfirstlane(row0), rows = __builtin_amdgcn_readfirstlane(rows);
 
     if (p.out_dst && (int)threadIdx.x < rows) {       // read long before the epilogue; the K loop's barriers publish it
         const int dst = p.out_dst[row0 + threadIdx.x];
@@ -59,14 +61,14 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 #pragma unroll
     for (int t = 0; t < kTN; ++t) {
         const int nt = tile_ok[t] ? ntile0 + t : 0;
-        b_ptr[t] = reinterpret_cast<const uint4 *>(w_e + (size_t)nt * (K / frag_k(BITS)) * kFragBytes) + lane;
+        b_ptr[t] = reinterpret_cast<const uint4 *>(w_e + (size_t)nt * (K / frag_k(BITS)) * kFragBytes);   // wave-uniform
     }
     const int G = K / p.g;
     const __half *s_ptr[kTN];
 #pragma unroll
     for (int t = 0; t < kTN; ++t) {
         const int nt = tile_ok[t] ? ntile0 + t : 0;
-        s_ptr[t] = p.scales + (size_t)e * G * N + nt * 32 + (lane & 31);
+        s_ptr[t] = p.scales + (size_t)e * G * N + nt * 32;              // wave-uniform
     }
 
     float16_t acc[TM][kTN];
@@ -86,54 +88,62 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     float16_t accg[ACC ? TM : 1][kTN];
 
     // Activations are fetched one K step ahead (they come from L2); packed weights and group
-    // scales two steps ahead, into two register sets used alternately (they come from HBM, and
-    // one step of MFMA work is shorter than that latency).
-    uint4 ga[TM], gb[2][kTN][NW];
-    _Float16 gs[2][kTN];
+    // scales PF = 2 steps ahead, into two register sets used alternately (they come from HBM, and
+    // one step of MFMA work is shorter than that latency).  The tallest 8-bit tile has registers
+    // for one set only and fetches one step ahead.
+    constexpr int PF = (BITS == 8 && TM == 4) ? 1 : 2;
+    uint4 ga[TM], gb[PF][kTN][NW];
+    _Float16 gs[PF][kTN];
     auto load_a = [&](int kb) {
 #pragma unroll
         for (int m = 0; m < TM; ++m) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kb * 64);
     };
     auto load_b = [&](int kb, auto slot_c) {
-        constexpr int SL = decltype(slot_c)::value;
+        constexpr int WS = decltype(slot_c)::value;
 #pragma unroll
         for (int t = 0; t < kTN; ++t) {
 #pragma unroll
-            for (int w = 0; w < NW; ++w) gb[SL][t][w] = b_ptr[t][(size_t)(kb * NW + w) * 64];
+            for (int w = 0; w < NW; ++w) gb[WS][t][w] = (b_ptr[t] + (size_t)(kb * NW + w) * 64)[lane];
             if (SMODE != SCALE_CHANNEL)
-                gs[SL][t] = __builtin_bit_cast(_Float16, s_ptr[t][(size_t)((kb * 64) / p.g) * N]);
+                gs[WS][t] = __builtin_bit_cast(_Float16, (s_ptr[t] + (size_t)((kb * 64) / p.g) * N)[lane & 31]);
         }
     };
 
     load_a(0);
     load_b(0, std::integral_constant<int, 0>{});
-    load_b(min(1, nk - 1), std::integral_constant<int, 1>{});
-    // Private copies of the two steps being computed.  They are taken (and the loads of the next
-    // two steps issued) once per pair of K steps, at the top of the loop body: at the loop edge
-    // every weight load is then at least a full step old, so the drain of the load counter that
-    // the compiler places at a loop head does not wait for fresh loads.
-    uint32_t raw2[2][kTN][NW * 4];
-    _Float16 sc2[2][kTN];
-    auto take_pair = [&](int kb) {
-        static_assert(true, "");
+    if constexpr (PF == 2) load_b(min(1, nk - 1), std::integral_constant<int, 1>{});
+    // Private copies of the steps being computed.  They are taken (and the loads of the next
+    // steps issued) once per pair of K steps, at the top of the loop body (PF = 1: at the top of
+    // each step): at the loop edge every weight load is then at least a full step old, so the
+    // drain of the load counter that the compiler places at a loop head does not wait for fresh loads.
+    uint32_t raw2[PF][kTN][NW * 4];
+    _Float16 sc2[PF][kTN];
+    auto take = [&](auto slot_c) {
+        constexpr int WS = decltype(slot_c)::value;
 #pragma unroll
-        for (int sl = 0; sl < 2; ++sl)
+        for (int t = 0; t < kTN; ++t) {
 #pragma unroll
-            for (int t = 0; t < kTN; ++t) {
-#pragma unroll
-                for (int w = 0; w < NW; ++w) {
-                    // real register moves (opaque to the compiler): if it merged these copies with
-                    // the load registers, the refills would land elsewhere and have to be moved
-                    // back at the loop edge, i.e. waited for right after being issued
-                    raw2[sl][t][4 * w + 0] = opaque_copy(gb[sl][t][w].x); raw2[sl][t][4 * w + 1] = opaque_copy(gb[sl][t][w].y);
-                    raw2[sl][t][4 * w + 2] = opaque_copy(gb[sl][t][w].z); raw2[sl][t][4 * w + 3] = opaque_copy(gb[sl][t][w].w);
-                }
-                sc2[sl][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[sl][t])));
+            for (int w = 0; w < NW; ++w) {
+                // real register moves (opaque to the compiler): if it merged these copies with
+                // the load registers, the refills would land elsewhere and have to be moved
+                // back at the loop edge, i.e. waited for right after being issued
+                raw2[WS][t][4 * w + 0] = opaque_copy(gb[WS][t][w].x); raw2[WS][t][4 * w + 1] = opaque_copy(gb[WS][t][w].y);
+                raw2[WS][t][4 * w + 2] = opaque_copy(gb[WS][t][w].z); raw2[WS][t][4 * w + 3] = opaque_copy(gb[WS][t][w].w);
             }
-        // (no branches around the loads: past the end they re-read the last step, which keeps the
-        // loop body free of joins and the load counter exact)
+            sc2[WS][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[WS][t])));
+        }
+    };
+    // (no branches around the loads: past the end they re-read the last step, which keeps the
+    // loop body free of joins and the load counter exact)
+    auto take_pair = [&](int kb) {
+        take(std::integral_constant<int, 0>{});
+        take(std::integral_constant<int, PF - 1>{});
         load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
-        load_b(min(kb + 3, nk - 1), std::integral_constant<int, 1>{});
+        load_b(min(kb + 3, nk - 1), std::integral_constant<int, PF - 1>{});
+    };
+    auto take_one = [&](int kb) {
+        take(std::integral_constant<int, 0>{});
+        load_b(min(kb + 1, nk - 1), std::integral_constant<int, 0>{});
     };
     auto k_step = [&](int kb, auto slot_c, auto live_c) {
         constexpr int SL = decltype(slot_c)::value;
@@ -157,8 +167,8 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
         }
         __syncthreads();
-        uint32_t (&raw)[kTN][NW * 4] = raw2[SL];
-        _Float16 (&sc)[kTN] = sc2[SL];
+        uint32_t (&raw)[kTN][NW * 4] = raw2[PF == 2 ? SL : 0];
+        _Float16 (&sc)[kTN] = sc2[PF == 2 ? SL : 0];
         load_a(min(kb + 1, nk - 1));
         __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of this step's MFMAs
 
@@ -192,17 +202,34 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         };
         // ---- MFMA over the four 16-deep steps of this K slab; the fragments of step j+1 are
         // converted while the MFMAs of step j run (VALU work hides under the matrix pipe)
+        // Where the registers allow (PIPE), the A fragments of step j+1 are read from LDS before the
+        // MFMAs of step j are issued, so that the LDS latency passes under a full step of matrix
+        // work; otherwise each fragment is read just before its MFMAs and the other wavefront of
+        // the SIMD covers the wait.
+        constexpr bool PIPE = TM < 4 || !(SMODE == SCALE_GROUP_SPLIT || (SMODE == SCALE_GROUP && ABF16 && BITS == 4));
         uint32_t bw[2][kTN][4], bl[2][kTN][4];
+        half8_t af[PIPE ? 2 : 1][TM];
+        auto read_a = [&](int j, int m) {
+            return *reinterpret_cast<const half8_t *>(stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
+        };
+        auto read_step = [&](int j, half8_t (&dst)[TM]) {
+#pragma unroll
+            for (int m = 0; m < TM; ++m)
+                if (m < LIVE) dst[m] = read_a(j, m);    // row tiles past the expert's last row are skipped
+        };
+        if (PIPE) read_step(0, af[0]);
         dequant_step(0, bw[0], bl[0]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+            if (PIPE && j + 1 < 4) {
+                read_step(j + 1, af[PIPE ? (j + 1) & 1 : 0]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (j + 1 < 4) dequant_step(j + 1, bw[(j + 1) & 1], bl[(j + 1) & 1]);
-            constexpr int JM = 1;
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
-                if (m < LIVE) {                         // row tiles past the expert's last row are skipped
-                    const half8_t af = *reinterpret_cast<const half8_t *>(
-                        stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
+                if (m < LIVE) {
+                    const half8_t a = PIPE ? af[PIPE ? j & 1 : 0][m] : read_a(j, m);
 #pragma unroll
                     for (int t = 0; t < kTN; ++t) {
                         if constexpr (ACC) {
@@ -210,11 +237,11 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                             if (SL == 0 && j == 0)          // first products of a group: start from zero
 #pragma unroll
                                 for (int i = 0; i < 16; ++i) c[i] = 0.0f;
-                            accg[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), c, 0, 0, 0);
+                            accg[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, frag_from(bw[j & 1][t]), c, 0, 0, 0);
                         } else {
-                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bw[j & JM][t]), acc[m][t], 0, 0, 0);
+                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, frag_from(bw[j & 1][t]), acc[m][t], 0, 0, 0);
                             if (SMODE == SCALE_GROUP_SPLIT)
-                                acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, frag_from(bl[j & JM][t]), acc[m][t], 0, 0, 0);
+                                acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, frag_from(bl[j & 1][t]), acc[m][t], 0, 0, 0);
                         }
                     }
                 }
@@ -236,9 +263,13 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     // holds few rows): a run-time test inside the loop would cut the MFMA stream into pieces.
     auto k_loop = [&](auto live_c) {
         for (int kb = 0; kb < nk; kb += 2) {
-            take_pair(kb);
+            if constexpr (PF == 2) take_pair(kb);
+            else take_one(kb);
             k_step(kb, std::integral_constant<int, 0>{}, live_c);
-            if (kb + 1 < nk) k_step(kb + 1, std::integral_constant<int, 1>{}, live_c);
+            if (kb + 1 < nk) {
+                if constexpr (PF == 1) take_one(kb + 1);
+                k_step(kb + 1, std::integral_constant<int, 1>{}, live_c);
+            }
         }
     };
     const int live = (rows + 31) / 32;

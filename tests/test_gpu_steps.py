@@ -153,6 +153,9 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
     ([9, 200, 0, 45], 256, 512, 4, 128, "bf16", torch.float32),
     ([64, 3], 128, 192, 8, 0, "bf16", torch.float32),
     ([150, 20], 256, 256, 4, 64, "bf16", torch.float32),
+    ([300, 70, 129], 256, 320, 8, 0, "f16", torch.float16),        # tallest 8-bit tiles (weights fetched one step ahead), rows dealt 96+96+96+12
+    ([290, 131], 128, 192, 8, 0, "bf16", torch.float32),
+    ([270, 257, 1], 192, 256, 4, 0, "f16", torch.float32),          # balanced row tiles: 96+96+78 and 96+96+65
 ])
 def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     _say(f"ffn rows={rows} d={d} F={F} bits={bits} g={g} {act} y={y_dt}")
