@@ -133,23 +133,23 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             sc2[WS][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[WS][t])));
         }
     };
-    // (no branches around the loads: past the end they re-read the last step, which keeps the
-    // loop body free of joins and the load counter exact)
-    auto take_pair = [&](int kb) {
-        take(std::integral_constant<int, 0>{});
-        take(std::integral_constant<int, PF - 1>{});
-        load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
-        load_b(min(kb + 3, nk - 1), std::integral_constant<int, PF - 1>{});
-    };
-    auto take_one = [&](int kb) {
-        take(std::integral_constant<int, 0>{});
-        load_b(min(kb + 1, nk - 1), std::integral_constant<int, 0>{});
-    };
-    auto k_step = [&](int kb, auto slot_c, auto live_c) {
+    // The refills are issued inside the step, after the activation loads of the next step: the
+    // load counter is in order, so a wait for those activations then leaves the younger weight
+    // loads in flight.  (No branches around the loads: past the end they re-read the last step,
+    // which keeps the loop body free of joins and the load counter exact.)
+    auto refill = [&](int kb, auto slot_c) {
         constexpr int SL = decltype(slot_c)::value;
-        constexpr int LIVE = decltype(live_c)::value;    // row tiles of this block that hold rows      // = kb & 1: LDS stage and weight register set
-        uint16_t *stage = lds_a[SL];
-        // ---- activations to LDS (bf16 rows are scaled by a power of two into FP16 range)
+        if constexpr (PF == 2) {
+            if constexpr (SL == 0) {
+                load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
+                load_b(min(kb + 3, nk - 1), std::integral_constant<int, PF - 1>{});
+            }
+        } else {
+            load_b(min(kb + 1, nk - 1), std::integral_constant<int, 0>{});
+        }
+    };
+    // registers -> LDS stage (bf16 rows are scaled by a power of two into FP16 range)
+    auto write_a = [&](uint16_t *stage) {
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
             uint4 v = ga[m];
@@ -166,10 +166,20 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             }
             *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
         }
+    };
+    // One barrier per step, at its top: it publishes this step's stage (written during the
+    // previous step) and tells that every wavefront has left the other stage, which is then
+    // refilled three quarters into the step, when its rows have had time to arrive; neither
+    // the arrival of the rows nor the LDS writes are waited for in front of a barrier.
+    auto k_step = [&](int kb, auto slot_c, auto live_c) {
+        constexpr int SL = decltype(slot_c)::value;      // = kb & 1: LDS stage and weight register set
+        constexpr int LIVE = decltype(live_c)::value;    // row tiles of this block that hold rows
+        uint16_t *stage = lds_a[SL];
         __syncthreads();
         uint32_t (&raw)[kTN][NW * 4] = raw2[PF == 2 ? SL : 0];
         _Float16 (&sc)[kTN] = sc2[PF == 2 ? SL : 0];
         load_a(min(kb + 1, nk - 1));
+        refill(kb, slot_c);
         __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of this step's MFMAs
 
         // unpack + convert one 16-deep step of weight fragments in registers
@@ -246,6 +256,11 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                     }
                 }
             }
+            if (j == 2) {
+                __builtin_amdgcn_sched_barrier(0);
+                write_a(lds_a[1 - SL]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         if constexpr (ACC && SL == 1) {                 // end of the group: acc += scale * accg
 #pragma unroll
@@ -263,15 +278,16 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     // holds few rows): a run-time test inside the loop would cut the MFMA stream into pieces.
     auto k_loop = [&](auto live_c) {
         for (int kb = 0; kb < nk; kb += 2) {
-            if constexpr (PF == 2) take_pair(kb);
-            else take_one(kb);
+            take(std::integral_constant<int, 0>{});
+            if constexpr (PF == 2) take(std::integral_constant<int, PF - 1>{});
             k_step(kb, std::integral_constant<int, 0>{}, live_c);
             if (kb + 1 < nk) {
-                if constexpr (PF == 1) take_one(kb + 1);
+                if constexpr (PF == 1) take(std::integral_constant<int, 0>{});
                 k_step(kb + 1, std::integral_constant<int, 1>{}, live_c);
             }
         }
     };
+    write_a(lds_a[0]);
     const int live = (rows + 31) / 32;
     if (TM == 1 || live == TM) k_loop(std::integral_constant<int, TM>{});
     else if (TM >= 4 && live == 3) k_loop(std::integral_constant<int, 3>{});
