@@ -133,21 +133,6 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             sc2[WS][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[WS][t])));
         }
     };
-    // The refills are issued inside the step, after the activation loads of the next step: the
-    // load counter is in order, so a wait for those activations then leaves the younger weight
-    // loads in flight.  (No branches around the loads: past the end they re-read the last step,
-    // which keeps the loop body free of joins and the load counter exact.)
-    auto refill = [&](int kb, auto slot_c) {
-        constexpr int SL = decltype(slot_c)::value;
-        if constexpr (PF == 2) {
-            if constexpr (SL == 0) {
-                load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
-                load_b(min(kb + 3, nk - 1), std::integral_constant<int, PF - 1>{});
-            }
-        } else {
-            load_b(min(kb + 1, nk - 1), std::integral_constant<int, 0>{});
-        }
-    };
     // registers -> LDS stage (bf16 rows are scaled by a power of two into FP16 range)
     auto write_a = [&](uint16_t *stage) {
 #pragma unroll
@@ -169,8 +154,8 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     };
     // One barrier per step, at its top: it publishes this step's stage (written during the
     // previous step) and tells that every wavefront has left the other stage, which is then
-    // refilled three quarters into the step, when its rows have had time to arrive; neither
-    // the arrival of the rows nor the LDS writes are waited for in front of a barrier.
+    // refilled at the end of the step, when its rows have had time to arrive; the arrival of
+    // the rows is not waited for in front of a barrier.
     auto k_step = [&](int kb, auto slot_c, auto live_c) {
         constexpr int SL = decltype(slot_c)::value;      // = kb & 1: LDS stage and weight register set
         constexpr int LIVE = decltype(live_c)::value;    // row tiles of this block that hold rows
@@ -178,9 +163,27 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         __syncthreads();
         uint32_t (&raw)[kTN][NW * 4] = raw2[PF == 2 ? SL : 0];
         _Float16 (&sc)[kTN] = sc2[PF == 2 ? SL : 0];
-        load_a(min(kb + 1, nk - 1));
-        refill(kb, slot_c);
-        __builtin_amdgcn_sched_barrier(0);              // the loads stay ahead of this step's MFMAs
+        // The step's loads are dealt over its four MFMA sub-steps, so that the memory pipeline
+        // takes a few at a time between matrix instructions: the next step's activation rows in
+        // the first two, the weight refills after them (the load counter is in order, so the wait
+        // for the rows leaves the younger weight loads in flight).  No branches around the loads:
+        // past the end they re-read the last step, which keeps the loop body free of joins and
+        // the load counter exact.
+        auto issue = [&](int j) {
+            const int kn = min(kb + 1, nk - 1);
+            if (j < 2) {
+#pragma unroll
+                for (int m = 0; m < TM; ++m)
+                    if (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0)) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
+            } else if constexpr (PF == 2) {
+                if constexpr (SL == 0) {
+                    if (j == 2) load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
+                    else load_b(min(kb + 3, nk - 1), std::integral_constant<int, 1>{});
+                }
+            } else if (j == 2) {
+                load_b(min(kb + 1, nk - 1), std::integral_constant<int, 0>{});
+            }
+        };
 
         // unpack + convert one 16-deep step of weight fragments in registers
         auto dequant_step = [&](int j, uint32_t (&bw)[kTN][4], uint32_t (&bl)[kTN][4]) {
@@ -231,10 +234,9 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         dequant_step(0, bw[0], bl[0]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (PIPE && j + 1 < 4) {
-                read_step(j + 1, af[PIPE ? (j + 1) & 1 : 0]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            issue(j);
+            if (PIPE && j + 1 < 4) read_step(j + 1, af[PIPE ? (j + 1) & 1 : 0]);
+            __builtin_amdgcn_sched_barrier(0);          // loads and LDS reads stay ahead of this sub-step's MFMAs
             if (j + 1 < 4) dequant_step(j + 1, bw[(j + 1) & 1], bl[(j + 1) & 1]);
 #pragma unroll
             for (int m = 0; m < TM; ++m) {
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                     }
                 }
             }
-            if (j == 2) {
+            if (j == 3) {
                 __builtin_amdgcn_sched_barrier(0);
                 write_a(lds_a[1 - SL]);
                 __builtin_amdgcn_sched_barrier(0);
