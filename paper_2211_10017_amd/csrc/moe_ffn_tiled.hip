@@ -134,9 +134,10 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         }
     };
     // registers -> LDS stage (bf16 rows are scaled by a power of two into FP16 range)
-    auto write_a = [&](uint16_t *stage) {
+    auto write_a = [&](uint16_t *stage, int live_tiles) {
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
+            if (m >= live_tiles) continue;
             uint4 v = ga[m];
             if (ABF16) {
                 uint32_t in[4] = {v.x, v.y, v.z, v.w}, o[4];
@@ -173,8 +174,8 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             const int kn = min(kb + 1, nk - 1);
             if (j < 2) {
 #pragma unroll
-                for (int m = 0; m < TM; ++m)
-                    if (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0)) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
+                for (int m = 0; m < TM; ++m)       // (row tiles past the expert's last row are neither loaded nor written)
+                    if (m < LIVE && (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0))) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
             } else if constexpr (PF == 2) {
                 if constexpr (SL == 0) {
                     if (j == 2) load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             }
             if (j == 3) {
                 __builtin_amdgcn_sched_barrier(0);
-                write_a(lds_a[1 - SL]);
+                write_a(lds_a[1 - SL], LIVE);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -289,8 +290,8 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             }
         }
     };
-    write_a(lds_a[0]);
     const int live = (rows + 31) / 32;
+    write_a(lds_a[0], live);
     if (TM == 1 || live == TM) k_loop(std::integral_constant<int, TM>{});
     else if (TM >= 4 && live == 3) k_loop(std::integral_constant<int, 3>{});
     else if (TM >= 2 && live == 2) k_loop(std::integral_constant<int, 2>{});
