@@ -201,17 +201,6 @@ __host__ __device__ constexpr int stage_vecs(int K) { return kUnrolledFitCap * (
 // the denominator of the Table 1 comparison).  NATIVE replaces the magic-number conversion by the
 // chip's integer-to-float conversion instructions (the variant Sec. 3.4.1 found too slow on its
 // hardware; kept for that comparison only).
-// 16 bytes per lane from global memory straight into LDS: lane l's bytes land at dst + 16 l, dst
-// the same for the whole wavefront.  Written as assembly so that the compiler's load counter
-// does not see it: it would otherwise take loads of two kinds to be in flight and wait for all
-// of them at the first use of any.  The caller waits (vmcnt) for it by hand; it is older than
-// every load the compiler counts, and the counter retires loads in order.
-__device__ inline void load_to_lds16(const void *src, uint16_t *dst)
-{
-    const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst;
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(l) : "memory", "m0");
-}
-
 template <int BITS, int KB, int TPW, int KS, bool NATIVE = false>
 __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int fit)
 {
@@ -250,21 +239,10 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 *a_vec = reinterpret_cast<const u32x4 *>(p.a + (size_t)lo * K);
     constexpr int NA = stage_vecs(K) < 1 ? 1 : stage_vecs(K);
-    // Rows of at least 1 KB go from global memory straight into LDS (a wavefront's 64 vectors are
-    // contiguous there, inside one row): no staging registers, so more wavefronts fit a SIMD.
-    // Vectors past the live rows (clamped reads) land in a per-thread dump slot behind the rows.
-    constexpr bool DMA = VPR % 64 == 0;
-    uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? 4 * 16 * 64 * 2 : 0);
-    u32x4 av[DMA ? 1 : NA];
+    u32x4 av[NA];
     static_for<0, NA>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
-        if constexpr (DMA) {
-            const int first = j * 256 + wave * 64;      // wave-uniform: one row, one LDS address
-            uint16_t *dst = first < total ? lds_a + (first / VPR) * LDR + (first % VPR) * 8 : dump + wave * 512;
-            load_to_lds16(a_vec + min(first + lane, total - 1), dst);
-        } else {
-            av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
-        }
+        av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
     });
     float cs[TPW], bias[TPW];
     const __half *bias_or_scale = p.bias ? p.bias : BITS == 16 ? reinterpret_cast<const __half *>(p.wq) : p.scales;   // no branch around a load
@@ -282,19 +260,14 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
         W[i] = wbase[wofs(i)];
         __builtin_amdgcn_sched_barrier(0);
     });
-    if constexpr (DMA) {
-        // this wavefront's rows are in LDS once at most the ring's kRing = 16 younger loads are
-        // outstanding: vmcnt(16) (expcnt and lgkmcnt fields left at "no wait")
-        static_assert(kRing == 16, "the wait below counts the ring's loads");
-        __builtin_amdgcn_s_waitcnt(0x4f70);
-    } else {
-        static_for<0, NA>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            const int idx = j * 256 + (int)threadIdx.x;
-            uint16_t *dst = idx < total ? lds_a + (idx / VPR) * LDR + (idx % VPR) * 8 : dump + threadIdx.x * 8;
-            *reinterpret_cast<u32x4 *>(dst) = av[j];
-        });
-    }
+    // vectors past the live rows (clamped reads above) land in a per-thread dump slot behind the rows
+    uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? 4 * 16 * 64 * 2 : 0) + threadIdx.x * 8;
+    static_for<0, NA>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        const int idx = j * 256 + (int)threadIdx.x;
+        uint16_t *dst = idx < total ? lds_a + (idx / VPR) * LDR + (idx % VPR) * 8 : dump;
+        *reinterpret_cast<u32x4 *>(dst) = av[j];
+    });
     __syncthreads();
     if (!has) return;
 
