@@ -157,6 +157,26 @@ __device__ inline void store_out(void *out, int dtype, size_t o, float v)
     else reinterpret_cast<_Float16 *>(out)[o] = (_Float16)v;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's bytes land at dst + 16 l, dst
+// the same for the whole wavefront.  Written as assembly so that the compiler's load counter
+// does not see it (it would take loads of two kinds to be in flight and wait for all of them at
+// the first use of any).  The caller waits for it by hand with wait_loads<N>(), N = the loads
+// issued after it that may stay in flight: the counter retires loads in order, and the waits the
+// compiler places for its own loads can only be stricter for the ones it does not see.
+__device__ inline void load_to_lds16(const void *src, uint16_t *dst)
+{
+    const uint32_t l = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)dst;
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(l) : "memory", "m0");
+}
+
+// s_waitcnt vmcnt(N) alone (the other counters' fields say "no wait")
+template <int N>
+__device__ inline void wait_loads()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+
 // Work distribution of the tiled kernel.  A work item is (expert, column block, row tile); the
 // items are ordered expert-major, then by column block, row tile fastest, so that neighbours in
 // the order share a weight column block (row tiles of one expert) or an activation row tile

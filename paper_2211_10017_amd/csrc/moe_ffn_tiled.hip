@@ -12,7 +12,9 @@
 
 namespace moe {
 
-constexpr int kLdsRow = 64 + 8;          // halfs per LDS row: 144-byte stride, conflict-free b128 reads
+constexpr int kLdsRow = 64;              // halfs per LDS row: one K step, no padding; the 16-byte chunks of a row are
+                                         // stored at position (k chunk) ^ ((row >> 1) & 7), which makes the b128
+                                         // fragment reads conflict-free and keeps a wavefront's 64 chunks contiguous
 constexpr int kTN = 2;                   // 32-channel tiles per wavefront
 
 template <int BITS, int SMODE, bool ABF16, int TM>
@@ -45,7 +47,10 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 
     // ---- global addresses
     // A: thread loads 16 bytes = 8 K values of row (tid/8 + 32*pass)
-    const int a_row = threadIdx.x >> 3, a_seg = (threadIdx.x & 7) * 8;
+    // thread t fills chunk position t & 7 of LDS row t >> 3 (+ 32 per pass); the K chunk that belongs
+    // there is (t & 7) ^ ((row >> 1) & 7), the same for every pass
+    const int a_row = threadIdx.x >> 3, a_pos = (threadIdx.x & 7) * 8;
+    const int a_seg = ((threadIdx.x & 7) ^ ((threadIdx.x >> 4) & 7)) * 8;
     const uint16_t *a_ptr[TM];
     float a_down[TM];
 #pragma unroll
@@ -92,6 +97,13 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     // one step of MFMA work is shorter than that latency).  The tallest 8-bit tile has registers
     // for one set only and fetches one step ahead.
     constexpr int PF = (BITS == 8 && TM == 4) ? 1 : 2;
+    // FP16 rows need no conversion and go from global memory straight into the LDS stage (DMA):
+    // no staging registers, no LDS write instructions.  bf16 rows pass through registers.
+    constexpr bool DMA = !ABF16;
+    constexpr int LB = kTN * NW + (SMODE != SCALE_CHANNEL ? kTN : 0);   // loads of one load_b()
+    auto dma_a = [&](int kb, uint16_t *stage, int m) {
+        load_to_lds16(a_ptr[m] + kb * 64, stage + (32 * m + 8 * wave) * kLdsRow);
+    };
     uint4 ga[TM], gb[PF][kTN][NW];
     _Float16 gs[PF][kTN];
     auto load_a = [&](int kb) {
@@ -109,7 +121,14 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         }
     };
 
-    load_a(0);
+    const int live = (rows + 31) / 32;
+    if constexpr (DMA) {
+#pragma unroll
+        for (int m = 0; m < TM; ++m)
+            if (m < live) dma_a(0, lds_a[0], m);
+    } else {
+        load_a(0);
+    }
     load_b(0, std::integral_constant<int, 0>{});
     if constexpr (PF == 2) load_b(min(1, nk - 1), std::integral_constant<int, 1>{});
     // Private copies of the steps being computed.  They are taken (and the loads of the next
@@ -150,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                 }
                 v = make_uint4(o[0], o[1], o[2], o[3]);
             }
-            *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_seg) = v;
+            *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_pos) = v;
         }
     };
     // One barrier per step, at its top: it publishes this step's stage (written during the
@@ -161,6 +180,9 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         constexpr int SL = decltype(slot_c)::value;      // = kb & 1: LDS stage and weight register set
         constexpr int LIVE = decltype(live_c)::value;    // row tiles of this block that hold rows
         uint16_t *stage = lds_a[SL];
+        // this wavefront's share of the stage has landed once only the weight refills issued after
+        // it (in the previous step) are still in flight
+        if constexpr (DMA) wait_loads<PF == 2 ? (SL == 1 ? 2 * LB : 0) : LB>();
         __syncthreads();
         uint32_t (&raw)[kTN][NW * 4] = raw2[PF == 2 ? SL : 0];
         _Float16 (&sc)[kTN] = sc2[PF == 2 ? SL : 0];
@@ -175,7 +197,10 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             if (j < 2) {
 #pragma unroll
                 for (int m = 0; m < TM; ++m)       // (row tiles past the expert's last row are neither loaded nor written)
-                    if (m < LIVE && (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0))) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
+                    if (m < LIVE && (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0))) {
+                        if constexpr (!DMA) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
+                        else dma_a(kn, lds_a[1 - SL], m);     // the other stage: every wavefront has left it
+                    }
             } else if constexpr (PF == 2) {
                 if constexpr (SL == 0) {
                     if (j == 2) load_b(min(kb + 2, nk - 1), std::integral_constant<int, 0>{});
@@ -224,7 +249,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         uint32_t bw[2][kTN][4], bl[2][kTN][4];
         half8_t af[PIPE ? 2 : 1][TM];
         auto read_a = [&](int j, int m) {
-            return *reinterpret_cast<const half8_t *>(stage + (32 * m + (lane & 31)) * kLdsRow + 16 * j + 8 * (lane >> 5));
+            return *reinterpret_cast<const half8_t *>(stage + (32 * m + (lane & 31)) * kLdsRow + 8 * ((2 * j + (lane >> 5)) ^ ((lane >> 1) & 7)));
         };
         auto read_step = [&](int j, half8_t (&dst)[TM]) {
 #pragma unroll
@@ -259,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                     }
                 }
             }
-            if (j == 3) {
+            if (!DMA && j == 3) {
                 __builtin_amdgcn_sched_barrier(0);
                 write_a(lds_a[1 - SL], LIVE);
                 __builtin_amdgcn_sched_barrier(0);
@@ -290,12 +315,12 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             }
         }
     };
-    const int live = (rows + 31) / 32;
-    write_a(lds_a[0], live);
+    if constexpr (!DMA) write_a(lds_a[0], live);
     if (TM == 1 || live == TM) k_loop(std::integral_constant<int, TM>{});
     else if (TM >= 4 && live == 3) k_loop(std::integral_constant<int, 3>{});
     else if (TM >= 2 && live == 2) k_loop(std::integral_constant<int, 2>{});
     else k_loop(std::integral_constant<int, 1>{});
+    if constexpr (DMA) wait_loads<0>();      // the last step's (unused) refill of the other stage must land before the block's LDS is given up
 
     // ---- epilogue: scale (per channel), bias, ReLU, store.  acc[m][t][i] is row
     // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
