@@ -195,7 +195,8 @@ __host__ __device__ constexpr int stage_vecs(int K) { return kUnrolledFitCap * (
 // KS = 4 splits the K range of a slab over the four wavefronts of the block (a slab of 64 blocks
 // would otherwise be one long, latency-bound stream per wavefront while most of the chip idles):
 // each wavefront accumulates a quarter of K, the four partial tiles meet in LDS and are added in a
-// fixed order.
+// fixed order.  With TPW = 2 the block does this for two slabs in turn and keeps both accumulator
+// tiles until the end, because the partial tiles take the LDS space of the rows.
 //
 // BITS = 16 streams unquantised fp16 weights in the same fragment layout (one MFMA step per block;
 // the denominator of the Table 1 comparison).  NATIVE replaces the magic-number conversion by the
@@ -261,7 +262,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
         __builtin_amdgcn_sched_barrier(0);
     });
     // vectors past the live rows (clamped reads above) land in a per-thread dump slot behind the rows
-    uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? 4 * 16 * 64 * 2 : 0) + threadIdx.x * 8;
+    uint16_t *dump = lds_a + max(fit * LDR, KS == 4 ? TPW * 4 * 16 * 64 * 2 : 0) + threadIdx.x * 8;
     static_for<0, NA>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         const int idx = j * 256 + (int)threadIdx.x;
@@ -273,11 +274,16 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
 
     const uint16_t *arow = lds_a + (size_t)min(lane & 31, rows - 1) * LDR + 8 * (lane >> 5) +
                            kq * KBW * FK;               // clamped to a live row
-    float *part = reinterpret_cast<float *>(lds_a);    // KS = 4: [wave][16][64] partial tiles, over the rows once they are used up
+    float *part = reinterpret_cast<float *>(lds_a);    // KS = 4: [slab][wave][16][64] partial tiles, over the rows once they are used up
     uint4 A[2][STEPS];
-    float16_t acc;
+    // KS = 4 keeps one accumulator tile per slab until the end: the partial tiles meet in the LDS
+    // space of the activation rows, which every slab still needs
+    constexpr int NACC = KS == 4 ? TPW : 1;
+    float16_t accs[NACC];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) accs[a][i] = 0.0f;
     void *out_rows = reinterpret_cast<char *>(p.out) + (size_t)lo * N * (p.out_dtype == MOE_F32 ? 4 : 2);
     auto fetch_a = [&](int slot, int kb) {
 #pragma unroll
@@ -298,6 +304,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
             else if (NATIVE) dequant8_native(raw[2 * j], raw[2 * j + 1], bw);
             else if (BITS == 4) dequant4(raw[j], bw);
             else dequant8(raw[2 * j], raw[2 * j + 1], bw);
+            float16_t &acc = accs[KS == 4 ? sl : 0];
             acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, A[b & 1][j]), frag_from(bw), acc, 0,
                                                          0, 0);
         }
@@ -307,6 +314,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
             const int n = (tile0 + sl) * 32 + (lane & 31);
             const int rbase = 4 * (lane >> 5);
             if constexpr (KS == 1) {
+                float16_t &acc = accs[0];
                 float v[16];
 #pragma unroll
                 for (int q = 0; q < 16; ++q) {
@@ -328,39 +336,42 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
                 if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
                 else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
                 else put(reinterpret_cast<uint16_t *>(out_rows));
-            } else {
-                // the four K-quarters meet in LDS; wavefront w then finishes accumulator registers
-                // 4w..4w+3 (rows rbase + 8w + 0..3), adding the quarters in the order 0, 1, 2, 3
-                static_assert(KS == 1 || TPW == 1, "the partial tiles overwrite the activation rows");
+            } else if constexpr (sl == TPW - 1) {
+                // after the last slab the four K-quarters of every slab meet in LDS; wavefront w then
+                // finishes accumulator registers 4w..4w+3 (rows rbase + 8w + 0..3) of each slab,
+                // adding the quarters in the order 0, 1, 2, 3
                 __syncthreads();                        // every wavefront is done with the rows
 #pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    part[(wave * 16 + q) * 64 + lane] = acc[q];
-                    acc[q] = 0.0f;
-                }
-                __syncthreads();
-                float v[4];
+                for (int a = 0; a < TPW; ++a)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float *src = part + ((wave * 4 + i) * 64 + lane);
-                    v[i] = ((src[0] + src[16 * 64]) + src[2 * 16 * 64]) + src[3 * 16 * 64];
-                    v[i] = v[i] * cs[sl] + bias[sl];
-                    v[i] = activate(v[i], p.act);
-                }
-                auto put = [&](auto *out) {
-                    size_t o = (size_t)(rbase + 8 * wave) * N + n;
+                    for (int q = 0; q < 16; ++q) part[((a * 4 + wave) * 16 + q) * 64 + lane] = accs[a][q];
+                __syncthreads();
+#pragma unroll
+                for (int a = 0; a < TPW; ++a) {
+                    const int na = (tile0 + a) * 32 + (lane & 31);
+                    float v[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        if (rbase + 8 * wave + i < rows) {
-                            if constexpr (std::is_same<decltype(out), uint16_t *>::value) out[o] = to_bf16_rne(v[i]);
-                            else out[o] = (std::remove_pointer_t<decltype(out)>)v[i];
-                        }
-                        o += N;
+                        const float *src = part + (a * 4 * 16 * 64 + (wave * 4 + i) * 64 + lane);
+                        v[i] = ((src[0] + src[16 * 64]) + src[2 * 16 * 64]) + src[3 * 16 * 64];
+                        v[i] = v[i] * cs[a] + bias[a];
+                        v[i] = activate(v[i], p.act);
                     }
-                };
-                if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
-                else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
-                else put(reinterpret_cast<uint16_t *>(out_rows));
+                    auto put = [&](auto *out) {
+                        size_t o = (size_t)(rbase + 8 * wave) * N + na;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (rbase + 8 * wave + i < rows) {
+                                if constexpr (std::is_same<decltype(out), uint16_t *>::value) out[o] = to_bf16_rne(v[i]);
+                                else out[o] = (std::remove_pointer_t<decltype(out)>)v[i];
+                            }
+                            o += N;
+                        }
+                    };
+                    if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
+                    else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
+                    else put(reinterpret_cast<uint16_t *>(out_rows));
+                }
             }
         }
     });
@@ -372,7 +383,7 @@ static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_
     constexpr int K = KB * (BITS == 4 ? 64 : BITS == 8 ? 32 : 16);
     // rows (KS = 4: or the partial tiles that later replace them) + the staging dump slots
     int lds = fit * (K + kRowPad) * 2;
-    if (KS == 4 && lds < 4 * 16 * 64 * 4) lds = 4 * 16 * 64 * 4;
+    if (KS == 4 && lds < TPW * 4 * 16 * 64 * 4) lds = TPW * 4 * 16 * 64 * 4;
     lds += 256 * 16;
     static bool raised = false;
     if (!raised) {
@@ -427,17 +438,20 @@ int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_
     const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
     const int fit = unrolled_fit_rows(p.K, most);
     if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: E=%d exceeds one launch", p.E);
-    // 16 blocks: one slab per wavefront; 64 blocks: one slab per block, K split over its wavefronts
+    // 16 blocks: one slab per wavefront; 64 blocks: K split over the block's wavefronts, two slabs per
+    // block (LDS holds two such blocks per CU: with one slab each the launch would need two rounds
+    // of blocks on the decode workload's fc2); every entry point takes N in multiples of 64 only
+    if (kb == 64 && (p.N / 32) % 2) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: N=%d is not a multiple of 64", p.N);
     if (bits == 4) {
         if (kb == 16) launch_unrolled<4, 16, 1, 1>(p, fit, most, s);
         else if (kb == 32) launch_unrolled<4, 32, 1, 1>(p, fit, most, s);
         else if (kb == 48) launch_unrolled<4, 48, 1, 1>(p, fit, most, s);
-        else launch_unrolled<4, 64, 1, 4>(p, fit, most, s);
+        else launch_unrolled<4, 64, 2, 4>(p, fit, most, s);
     } else {
         if (kb == 16) launch_unrolled<8, 16, 1, 1>(p, fit, most, s);
         else if (kb == 32) launch_unrolled<8, 32, 1, 1>(p, fit, most, s);
         else if (kb == 48) launch_unrolled<8, 48, 1, 1>(p, fit, most, s);
-        else launch_unrolled<8, 64, 1, 4>(p, fit, most, s);
+        else launch_unrolled<8, 64, 2, 4>(p, fit, most, s);
     }
     return check_launch("moe_grouped_ffn_wq (straight-line streaming gemm)");
 }

@@ -156,6 +156,7 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
     ([300, 70, 129], 256, 320, 8, 0, "f16", torch.float16),        # tallest 8-bit tiles (weights fetched one step ahead), rows dealt 96+96+96+12
     ([290, 131], 128, 192, 8, 0, "bf16", torch.float32),
     ([270, 257, 1], 192, 256, 4, 0, "f16", torch.float32),          # balanced row tiles: 96+96+78 and 96+96+65
+    ([2, 11, 5], 256, 2048, 8, 0, "f16", torch.float16),            # fc2 splits K over the wavefronts, two channel tiles per block
 ])
 def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     _say(f"ffn rows={rows} d={d} F={F} bits={bits} g={g} {act} y={y_dt}")
