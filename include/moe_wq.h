@@ -178,6 +178,31 @@ int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_
                               int out_dtype, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * moe_permute and moe_grouped_ffn_wq in one call, for decode-sized batches (Sec. 3.3 steps 2 and
+ * 3; the stable sort by expert is rebuilt inside the first GEMM).  fc1's blocks count the
+ * assignments of their expert and of the experts before it from expert_idx, fetch their rows
+ * straight from x and write the index arrays; fc2 (and moe_combine afterwards) read them as
+ * after moe_permute.  No x_perm copy and no permute launch.
+ *   x [T,d] fp16 (un-permuted, device); expert_idx [T*k] from moe_gate_topk (E = pruned row);
+ *   outputs: y_perm [R,d] in y_dtype, perm_src [R], inv_perm [R], expert_offsets [E+1]
+ *   (identical to what moe_permute writes, pruned rows behind the active ones,
+ *   expert_offsets[E] = active rows); workspace as for moe_grouped_ffn_wq with R = T*k.
+ * moe_grouped_ffn_wq_gated_supported returns 1 when a call with these sizes is taken: fp16
+ * activations, per-channel scales, T*k <= 256, and d such that fc1 runs in the straight-line
+ * streaming kernel (d = 1024 or 2048 with 4-bit, 512 or 1024 with 8-bit weights) under the
+ * row bound T.  Otherwise the call returns MOE_ERR_UNSUPPORTED and nothing is launched.
+ */
+int moe_grouped_ffn_wq_gated_supported(int T, int k, int E, int d, int F, int bits, int group_size,
+                                       int act_dtype);
+int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx, int T, int k,
+                             int E, int d, int F, int bits, int group_size, int activation,
+                             const void *w1_packed, const void *s1, const void *b1,
+                             const void *w2_packed, const void *s2, const void *b2, void *y_perm,
+                             int y_dtype, int32_t *perm_src, int32_t *inv_perm,
+                             int32_t *expert_offsets, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
+/*
  * Table 1 (Sec. 4.1): throughput of one grouped GEMM  y[r] = x_perm[r] @ deq(W[e])  on about 40
  * tokens spread over 1..32 active experts, with fp16, int8 and int4 weights.  This entry runs
  * that single GEMM with the decode-sized streaming kernels of moe_grouped_ffn_wq:

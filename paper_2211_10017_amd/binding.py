@@ -21,7 +21,8 @@ _DT = {torch.float16: MOE_F16, torch.bfloat16: MOE_BF16, torch.float32: MOE_F32}
 EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
            "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
            "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq",
-           "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed"]
+           "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed",
+           "moe_grouped_ffn_wq_gated_supported", "moe_grouped_ffn_wq_gated"]
 
 _lib = None
 ACTIVATIONS = {"relu": 0, "gelu": 1}     # MOE_ACT_RELU, MOE_ACT_GELU
@@ -61,6 +62,11 @@ def load():
     lib.moe_grouped_ffn_wq_routed.restype = i
     lib.moe_grouped_ffn_wq_routed.argtypes = [vp, i, vp, i, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i,
                                               vp, sz, vp]
+    lib.moe_grouped_ffn_wq_gated_supported.restype = i
+    lib.moe_grouped_ffn_wq_gated_supported.argtypes = [i, i, i, i, i, i, i, i]
+    lib.moe_grouped_ffn_wq_gated.restype = i
+    lib.moe_grouped_ffn_wq_gated.argtypes = [vp, i, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, vp,
+                                             vp, sz, vp]
     lib.moe_pack_fp16_experts.restype = i
     lib.moe_pack_fp16_experts.argtypes = [vp, i, i, i, vp, vp]
     lib.moe_grouped_gemm_wq.restype = i
@@ -247,3 +253,29 @@ def moe_grouped_ffn_wq_routed(x, perm_src, k: int, expert_offsets, E: int, d: in
         _ptr(b2, torch.float16, "b2"), _ptr(out), _DT[out.dtype], _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moe_grouped_ffn_wq_routed")
     return out
+
+
+def moe_grouped_ffn_wq_gated_supported(T: int, k: int, E: int, d: int, F: int, bits: int, group_size: int, act_dtype) -> bool:
+    return bool(load().moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, _DT[act_dtype]))
+
+
+def moe_grouped_ffn_wq_gated(x, expert_idx, E: int, d: int, F: int, bits: int, group_size: int, w1_packed, s1, w2_packed,
+                             s2, b1=None, b2=None, y_dtype=None, workspace=None, activation: str = "relu"):
+    """Decode-sized batches: permute + FFN in one call.  Returns (y_perm, perm_src, inv_perm, expert_offsets)."""
+    T, k = expert_idx.shape
+    R = T * k
+    dev = x.device
+    y = torch.empty((R, d), dtype=y_dtype or x.dtype, device=dev)
+    perm_src = torch.empty(R, dtype=torch.int32, device=dev)
+    inv_perm = torch.empty(R, dtype=torch.int32, device=dev)
+    offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, x.dtype), dtype=torch.uint8, device=dev)
+    rc = load().moe_grouped_ffn_wq_gated(
+        _ptr(x, torch.float16, "x"), _DT[x.dtype], _ptr(expert_idx, torch.int32, "expert_idx"), T, k, E, d, F, bits,
+        group_size, ACTIVATIONS[activation], _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"),
+        _ptr(b1, torch.float16, "b1"), _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"),
+        _ptr(b2, torch.float16, "b2"), _ptr(y), _DT[y.dtype], _ptr(perm_src), _ptr(inv_perm), _ptr(offsets),
+        _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "moe_grouped_ffn_wq_gated")
+    return y, perm_src, inv_perm, offsets

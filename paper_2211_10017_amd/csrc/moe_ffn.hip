@@ -81,8 +81,10 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     if (stream_ok && (max_rows <= 64 || few)) {
         g.row_hi = 0x7fffffff;                 // every expert streams, `fit` rows per block
         if (unrolled) return launch_stream_unrolled(g, bits, max_rows, s);
+        if (g.gate_idx) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel", g.K);
         return launch_stream_gemm(g, bits, smode, max_rows, s);
     }
+    if (g.gate_idx) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: these sizes do not run in the straight-line kernel");
     if (stream_ok && mean <= 96) {
         g.row_hi = fit;
         int rc = launch_stream_gemm(g, bits, smode, max_rows, s);
@@ -114,7 +116,9 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
                     const void *s1, const void *b1, const void *w2_packed, const void *s2,
                     const void *b2, void *y_perm, int y_dtype, void *workspace,
                     size_t workspace_bytes, void *stream,
-                    const int32_t *perm_src, int k, const float *expert_scale)
+                    const int32_t *perm_src, int k, const float *expert_scale,
+                    const int32_t *gate_idx = nullptr, int32_t *perm_src_out = nullptr, int32_t *inv_perm_out = nullptr,
+                    int32_t *offsets_out = nullptr)
 {
     using namespace moe;
     if (!expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || (R != 0 && (!x_perm || !y_perm)))
@@ -154,6 +158,10 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     g1.out = h; g1.E = E; g1.R = R; g1.K = d; g1.N = F; g1.g = grouped ? group_size : d;
     g1.out_dtype = act_dtype; g1.act = activation;
     g1.a_src = perm_src; g1.a_div = k;
+    if (gate_idx) {     // decode-sized: fc1 rebuilds the permutation from the gate's output and writes the index arrays
+        g1.gate_idx = gate_idx; g1.n_assign = R; g1.gate_k = k;
+        g1.perm_src_out = perm_src_out; g1.inv_perm_out = inv_perm_out; g1.offsets_out = offsets_out;
+    }
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, R, d, pow_x);
         int rc = check_launch("moe_grouped_ffn_wq (row scale x)");
@@ -171,6 +179,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     g2.out = y_perm; g2.K = F; g2.N = d; g2.g = grouped ? group_size : F;
     g2.out_dtype = y_dtype; g2.act = MOE_ACT_NONE;
     g2.a_src = nullptr;
+    g2.gate_idx = nullptr;
     if (expert_scale) { g2.out_dst = perm_src; g2.out_scale = expert_scale; }
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)h, R, F, pow_h);
@@ -221,6 +230,47 @@ extern "C" int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int
                                          "which take permuted rows only: use moe_permute + moe_grouped_ffn_wq + moe_combine");
     return ffn_impl(x, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, activation, w1_packed, s1, b1,
                     w2_packed, s2, b2, out, out_dtype, workspace, workspace_bytes, stream, perm_src, k, expert_scale);
+}
+
+// Decode-sized batches: moe_permute and moe_grouped_ffn_wq in one call.  fc1 runs in the straight-line
+// streaming kernel, whose blocks rebuild the permutation from the gate's expert indices, fetch their
+// rows from the tokens and write perm_src / inv_perm / expert_offsets on the way; fc2 and moe_combine
+// then read those arrays as after moe_permute.
+static bool gated_shapes(int T, int k, int E, int d, int F, int bits, int group_size, int act_dtype)
+{
+    using namespace moe;
+    if (T <= 0 || k < 1 || k > 2 || E <= 0 || d <= 0 || F <= 0 || act_dtype != MOE_F16) return false;
+    if ((long)T * k > kGatedMaxAssign || (bits != 4 && bits != 8) || d % 64 || F % 64) return false;
+    if (group_size != 0 && !(group_size == d && group_size == F)) return false;
+    if (!stream_unrolled_supports(d, bits, SCALE_CHANNEL) || !stream_unrolled_takes_gate(d, bits)) return false;
+    // the dispatch rule of run_gemm must send fc1 to the straight-line kernel alone (row bound T)
+    const int R = T * k, mean = (R + E - 1) / E;
+    return T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(d, T));
+}
+
+extern "C" int moe_grouped_ffn_wq_gated_supported(int T, int k, int E, int d, int F, int bits, int group_size,
+                                                  int act_dtype)
+{
+    return gated_shapes(T, k, E, d, F, bits, group_size, act_dtype) ? 1 : 0;
+}
+
+extern "C" int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx, int T, int k,
+                                        int E, int d, int F, int bits, int group_size, int activation,
+                                        const void *w1_packed, const void *s1, const void *b1,
+                                        const void *w2_packed, const void *s2, const void *b2, void *y_perm,
+                                        int y_dtype, int32_t *perm_src, int32_t *inv_perm,
+                                        int32_t *expert_offsets, void *workspace, size_t workspace_bytes,
+                                        void *stream)
+{
+    using namespace moe;
+    if (!expert_idx || !perm_src || !inv_perm || !expert_offsets)
+        return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq_gated: NULL pointer");
+    if (!gated_shapes(T, k, E, d, F, bits, group_size, act_dtype))
+        return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: only decode-sized fp16 batches with per-channel scales "
+                                         "(T*k <= %d) are taken: use moe_permute + moe_grouped_ffn_wq", kGatedMaxAssign);
+    return ffn_impl(x, act_dtype, expert_offsets, T * k, E, T, d, F, bits, group_size, activation, w1_packed, s1, b1,
+                    w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, k, nullptr,
+                    expert_idx, perm_src, inv_perm, expert_offsets);
 }
 
 // One grouped GEMM of the decode-sized case, for the comparison of Table 1 (fp16 / int8 / int4

@@ -30,7 +30,15 @@ struct GemmArgs {
     int a_div;
     const int32_t *out_dst;   // [R] or null: row r of the result goes to out[out_dst[r]], times out_scale[out_dst[r]]
     const float *out_scale;
+    // straight-line streaming kernel only (decode-sized batches): the permutation is rebuilt from the
+    // gate's output inside the launch.  gate_idx[a] is the expert of assignment a (E = pruned row),
+    // row a / gate_k of `a` is its token; the first block of every expert writes the index arrays.
+    const int32_t *gate_idx;  // [n_assign] or null
+    int n_assign, gate_k;
+    int32_t *perm_src_out, *inv_perm_out, *offsets_out;
 };
+
+constexpr int kGatedMaxAssign = 256;    // assignments the fused permutation takes: one per thread of a block
 
 int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);
 int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hipStream_t s);
@@ -38,6 +46,7 @@ bool stream_gemm_supports(int K, int bits, int smode);
 int stream_gemm_fit_rows(int K);
 bool stream_unrolled_supports(int K, int bits, int smode);
 int stream_unrolled_fit(int K, int max_rows);
+bool stream_unrolled_takes_gate(int K, int bits);
 int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s);
 int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s);
 

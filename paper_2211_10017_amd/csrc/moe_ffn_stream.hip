@@ -202,7 +202,14 @@ __host__ __device__ constexpr int stage_vecs(int K) { return kUnrolledFitCap * (
 // the denominator of the Table 1 comparison).  NATIVE replaces the magic-number conversion by the
 // chip's integer-to-float conversion instructions (the variant Sec. 3.4.1 found too slow on its
 // hardware; kept for that comparison only).
-template <int BITS, int KB, int TPW, int KS, bool NATIVE = false>
+//
+// PERM (decode-sized batches, at most 256 assignments): the launch takes the gate's expert indices
+// instead of a permuted copy of the rows.  Every block counts, with two ballots per wavefront, the
+// assignments of its expert and of the experts before it (the stable sort of Sec. 3.3 restricted to
+// what this block needs), fetches its rows straight from the tokens, and the first block of each
+// expert writes that expert's part of perm_src, inv_perm and expert_offsets for the launches after
+// this one.  Pruned rows (index E) are numbered behind the active ones by the last expert's block.
+template <int BITS, int KB, int TPW, int KS, bool NATIVE = false, bool PERM = false>
 __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int fit)
 {
     constexpr int STEPS = BITS == 4 ? 4 : BITS == 8 ? 2 : 1;
@@ -218,7 +225,50 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     const int e = blockIdx.y, z = blockIdx.z;
     const int N = p.N;
     int e_lo, e_hi;
-    expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
+    __shared__ int s_cnt[3][4];                 // per wavefront: assignments of this expert, of earlier experts, pruned
+    __shared__ int s_tok[kUnrolledFitCap];      // token of each row of this block
+    if constexpr (PERM) {
+        const int a = threadIdx.x;
+        const int v = a < p.n_assign ? p.gate_idx[a] : 0x7fffffff;
+        const bool mine = v == e, before = v < e, pruned = v == p.E;
+        const uint64_t m_mine = __ballot(mine), m_before = __ballot(before), m_pruned = __ballot(pruned);
+        if (lane == 0) {
+            s_cnt[0][wave] = __popcll(m_mine);
+            s_cnt[1][wave] = __popcll(m_before);
+            s_cnt[2][wave] = __popcll(m_pruned);
+        }
+        __syncthreads();
+        int first = 0, count = 0, lower = 0, pruned_first = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) { first += s_cnt[0][w]; pruned_first += s_cnt[2][w]; }
+            count += s_cnt[0][w];
+            lower += s_cnt[1][w];
+        }
+        const uint64_t below = (1ull << lane) - 1;
+        const int rank = first + __popcll(m_mine & below);           // stable: assignments in ascending order
+        e_lo = lower;
+        e_hi = lower + count;
+        if (blockIdx.x == 0 && z == 0) {
+            if (threadIdx.x == 0) {
+                p.offsets_out[e] = lower;
+                if (e == p.E - 1) p.offsets_out[p.E] = lower + count;   // = the active rows
+            }
+            if (mine) {
+                p.inv_perm_out[a] = lower + rank;
+                p.perm_src_out[lower + rank] = a;
+            }
+            if (pruned && e == p.E - 1) {
+                const int r = lower + count + pruned_first + __popcll(m_pruned & below);
+                p.inv_perm_out[a] = r;
+                p.perm_src_out[r] = a;
+            }
+        }
+        if (mine && rank >= z * fit && rank < z * fit + fit) s_tok[rank - z * fit] = a / p.gate_k;
+        __syncthreads();
+    } else {
+        expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
+    }
     const int m = e_hi - e_lo;
     if (m <= 0 || m > p.row_hi || z * fit >= m) return;   // same for the whole block
     const int lo = e_lo + z * fit;
@@ -238,12 +288,14 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     // from moving the small loads behind the ring or shuffling the ring's order
     const int total = rows * VPR;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 *a_vec = reinterpret_cast<const u32x4 *>(p.a + (size_t)lo * K);
+    const u32x4 *a_vec = reinterpret_cast<const u32x4 *>(p.a + (PERM ? 0 : (size_t)lo * K));
     constexpr int NA = stage_vecs(K) < 1 ? 1 : stage_vecs(K);
     u32x4 av[NA];
     static_for<0, NA>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
-        av[j] = a_vec[min(j * 256 + (int)threadIdx.x, total - 1)];
+        const int idx = min(j * 256 + (int)threadIdx.x, total - 1);
+        if constexpr (PERM) av[j] = a_vec[(size_t)s_tok[idx / VPR] * VPR + idx % VPR];   // row idx / VPR of the block is a token's row
+        else av[j] = a_vec[idx];
     });
     float cs[TPW], bias[TPW];
     const __half *bias_or_scale = p.bias ? p.bias : BITS == 16 ? reinterpret_cast<const __half *>(p.wq) : p.scales;   // no branch around a load
@@ -377,7 +429,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     });
 }
 
-template <int BITS, int KB, int TPW, int KS, bool NATIVE = false>
+template <int BITS, int KB, int TPW, int KS, bool NATIVE = false, bool PERM = false>
 static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_t s)
 {
     constexpr int K = KB * (BITS == 4 ? 64 : BITS == 8 ? 32 : 16);
@@ -387,14 +439,14 @@ static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_
     lds += 256 * 16;
     static bool raised = false;
     if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE, PERM>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         raised = true;
     }
     const int ntiles = p.N / 32;
     const int per_block = KS == 1 ? 4 * TPW : TPW;
     dim3 grid((ntiles + per_block - 1) / per_block, p.E, (max_rows + fit - 1) / fit);
-    hipLaunchKernelGGL((stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE>), grid, dim3(256), lds, s, p, fit);
+    hipLaunchKernelGGL((stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE, PERM>), grid, dim3(256), lds, s, p, fit);
 }
 
 // Rows per block of the straight-line kernel: what one staging pass (kStageVecs vectors per
@@ -415,6 +467,13 @@ bool stream_unrolled_supports(int K, int bits, int smode)
 }
 
 int stream_unrolled_fit(int K, int max_rows) { return unrolled_fit_rows(K, max_rows); }
+
+// Slab lengths for which the straight-line kernel is also built with the permutation inside.
+bool stream_unrolled_takes_gate(int K, int bits)
+{
+    const int kb = K / (bits == 4 ? 64 : 32);
+    return (bits == 4 || bits == 8) && K % (bits == 4 ? 64 : 32) == 0 && (kb == 16 || kb == 32);
+}
 
 // The Table 1 variants: fp16 weights (bits = 16) and the native integer-to-float conversion.
 int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s)
@@ -442,6 +501,15 @@ int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_
     // block (LDS holds two such blocks per CU: with one slab each the launch would need two rounds
     // of blocks on the decode workload's fc2); every entry point takes N in multiples of 64 only
     if (kb == 64 && (p.N / 32) % 2) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: N=%d is not a multiple of 64", p.N);
+    if (p.gate_idx) {                           // permutation rebuilt inside the launch
+        if (p.n_assign > kGatedMaxAssign || !stream_unrolled_takes_gate(p.K, bits))
+            return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: no kernel for K=%d bits=%d with %d assignments", p.K, bits, p.n_assign);
+        if (bits == 4 && kb == 16) launch_unrolled<4, 16, 1, 1, false, true>(p, fit, most, s);
+        else if (bits == 4) launch_unrolled<4, 32, 1, 1, false, true>(p, fit, most, s);
+        else if (kb == 16) launch_unrolled<8, 16, 1, 1, false, true>(p, fit, most, s);
+        else launch_unrolled<8, 32, 1, 1, false, true>(p, fit, most, s);
+        return check_launch("moe_grouped_ffn_wq_gated (straight-line streaming gemm)");
+    }
     if (bits == 4) {
         if (kb == 16) launch_unrolled<4, 16, 1, 1>(p, fit, most, s);
         else if (kb == 32) launch_unrolled<4, 32, 1, 1>(p, fit, most, s);

@@ -46,6 +46,8 @@ class MoEExpertLayer:
         # large batches: the row gather (and for k = 1 the un-permute and gate scale) run inside
         # the GEMMs instead of as copies of their own
         self.routed = bool(fuse_routing) and B.moe_grouped_ffn_wq_routed_supported(R, E, T, d, F, bits, group_size, act_dtype)
+        # decode-sized batches: the permutation is rebuilt inside fc1 (no permute launch, no x_perm copy)
+        self.gated = bool(fuse_routing) and B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, act_dtype)
 
     # -- offline: quantise one expert matrix from its fp32 master (which = 1 | 2) ------------
     def load_expert(self, which: int, e: int, w_fp32, q_canon_out=None):
@@ -123,6 +125,13 @@ class MoEExpertLayer:
                                     int(self.renormalize), p(self.expert_idx), p(self.expert_scale), st), "moe_gate_topk")
         combine = (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), active, self.T, self.k,
                                      self.d, p(self.out), odt, st), "moe_combine")
+        if self.gated:
+            ffn = (lib.moe_grouped_ffn_wq_gated,
+                   (p(x), dt, p(self.expert_idx), self.T, self.k, self.E, self.d, self.F, self.bits, self.group_size,
+                    self.activation, p(self.w1_packed), p(self.s1), p(self.b1), p(self.w2_packed), p(self.s2), p(self.b2),
+                    p(self.y_perm), ydt, p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_ffn),
+                    self.ws_ffn.numel(), st), "moe_grouped_ffn_wq_gated")
+            return [gate, ffn, combine]
         if self.routed:
             # index only (no x_perm copy); fc1 gathers, and fc2 scatters when there is one expert per
             # token and no pruned row (a pruned token's output row would stay unwritten)

@@ -11,6 +11,7 @@ import torch
 
 import oracle
 from helpers import MAX_ABS_TOL, REL_L2_TOL, Prepared, error_metrics, oracle_dtype_code, to_dev
+from paper_2211_10017_amd import binding as B
 from paper_2211_10017_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -32,7 +33,13 @@ def _check_layer(prep, sample_tokens):
     assert np.array_equal(layer.expert_offsets.cpu().numpy(), off)
     assert np.array_equal(layer.perm_src.cpu().numpy(), perm_src)
     assert np.array_equal(layer.inv_perm.cpu().numpy(), inv_perm)
-    if not layer.routed:                                          # (routed layers gather inside fc1: no x_perm copy)
+    if layer.gated:          # (the permutation is rebuilt inside fc1: the separate call is checked here, copy included)
+        xp_d, ps_d, ip_d, of_d = B.moe_permute(layer.expert_idx, prep.x_dev, w.E)
+        torch.cuda.synchronize()
+        assert np.array_equal(xp_d.float().cpu().numpy(), prep.x[perm_src // w.k])
+        assert np.array_equal(ps_d.cpu().numpy(), perm_src) and np.array_equal(ip_d.cpu().numpy(), inv_perm)
+        assert np.array_equal(of_d.cpu().numpy(), off)
+    elif not layer.routed:                                        # (routed layers gather inside fc1: no x_perm copy)
         xp = layer.x_perm.float().cpu().numpy()
         assert np.array_equal(xp, prep.x[perm_src // w.k])
     # layer output
@@ -85,7 +92,12 @@ def test_config_with_pruned_rows(name):
     assert np.array_equal(layer.inv_perm.cpu().numpy(), res["inv_perm"])
     active = int(res["expert_offsets"][w.E])
     assert 0 < active < w.R
-    assert np.array_equal(layer.x_perm.float().cpu().numpy()[:active], res["x_perm"][:active])
+    if layer.gated:
+        xp_d = B.moe_permute(layer.expert_idx, prep.x_dev, w.E)[0]
+        torch.cuda.synchronize()
+        assert np.array_equal(xp_d.float().cpu().numpy()[:active], res["x_perm"][:active])
+    else:
+        assert np.array_equal(layer.x_perm.float().cpu().numpy()[:active], res["x_perm"][:active])
     got = out.float().cpu().numpy()
     assert not got[fin == 1].any()                               # exactly zero
     max_abs, rel = error_metrics(got, res["out"])

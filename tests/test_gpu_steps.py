@@ -358,6 +358,52 @@ def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g):
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
 
+@pytest.mark.parametrize("T,k,E,d,F,bits,prune", [(64, 2, 32, 1024, 4096, 4, 0),     # the decode workload's shape
+                                                   (40, 2, 5, 1024, 256, 4, 7),        # few experts: several row groups per expert, pruned rows
+                                                   (256, 1, 8, 512, 2048, 8, 0),       # most assignments one launch takes
+                                                   (37, 1, 9, 1024, 128, 8, 11),       # 8-bit slabs of 32 blocks, empty experts likely
+                                                   (3, 2, 64, 2048, 128, 4, 1)])       # 4-bit slabs of 32 blocks, nearly every expert empty
+def test_gated_ffn_matches_oracle(T, k, E, d, F, bits, prune):
+    """Permutation rebuilt inside fc1: index arrays bit-exact with the oracle's stable sort, y_perm within tolerance."""
+    _say(f"gated ffn T={T} k={k} E={E} d={d} F={F} bits={bits} pruned={prune}")
+    rng = np.random.default_rng(T * 3 + E + bits + prune)
+    x = rng.standard_normal((T, d)).astype(np.float16).astype(np.float32)
+    wg = (rng.standard_normal((d, E)) * 0.05).astype(np.float16).astype(np.float32)
+    w1 = (rng.standard_normal((E, d, F)) * 0.05).astype(np.float32)
+    w2 = (rng.standard_normal((E, F, d)) * 0.05).astype(np.float32)
+    finished = np.zeros(T, dtype=np.uint8)
+    finished[rng.choice(T, size=prune, replace=False)] = 1
+    q1, s1 = oracle.quantize(w1, bits, 0)
+    q2, s2 = oracle.quantize(w2, bits, 0)
+    idx_o, _ = oracle.gate(x, wg, None, k, True, finished=finished if prune else None)
+    perm_src_o, inv_perm_o, off_o = oracle.permute(idx_o, E)
+    active = int(off_o[E])
+    x_perm_o = oracle.gather_rows(x, perm_src_o[:active], k)
+    y_o = oracle.grouped_ffn(x_perm_o, off_o, q1, s1, q2, s2, 0, oracle.F16)
+    _, ds1, p1 = B.moe_quantize_experts(to_dev(w1, torch.float32), bits, 0, want_canon=False)
+    _, ds2, p2 = B.moe_quantize_experts(to_dev(w2, torch.float32), bits, 0, want_canon=False)
+    xd = to_dev(x, torch.float16)
+    assert B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, 0, torch.float16)
+    idx, _ = B.moe_gate_topk(xd, to_dev(wg, torch.float16), None, k, True, finished=to_dev(finished, torch.uint8) if prune else None)
+    assert np.array_equal(idx.cpu().numpy(), idx_o)
+    y, ps, ip, of = B.moe_grouped_ffn_wq_gated(xd, idx, E, d, F, bits, 0, p1, ds1, p2, ds2, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert np.array_equal(of.cpu().numpy(), off_o)
+    assert np.array_equal(ps.cpu().numpy(), perm_src_o) and np.array_equal(ip.cpu().numpy(), inv_perm_o)
+    max_abs, rel = error_metrics(y.cpu().numpy()[:active], y_o)
+    _say(f"   active rows {active} of {T * k}; max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+def test_gated_ffn_refuses_other_sizes():
+    _say("gated ffn: what the fused permutation does not take is refused")
+    assert not B.moe_grouped_ffn_wq_gated_supported(512, 1, 8, 1024, 4096, 4, 0, torch.float16)      # more than 256 assignments
+    assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 128, torch.float16)    # group scales
+    assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, torch.bfloat16)     # bf16 rows
+    assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 4096, 4096, 4, 0, torch.float16)      # fc1 slabs of 64 blocks
+    assert B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, torch.float16)
+
+
 def test_routed_ffn_refuses_decode_sizes():
     _say("routed ffn: decode sizes are refused")
     assert not B.moe_grouped_ffn_wq_routed_supported(128, 32, 64, 1024, 4096, 4, 0, torch.float16)
