@@ -187,14 +187,22 @@ int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_
  *   outputs: y_perm [R,d] in y_dtype, perm_src [R], inv_perm [R], expert_offsets [E+1]
  *   (identical to what moe_permute writes, pruned rows behind the active ones,
  *   expert_offsets[E] = active rows); workspace as for moe_grouped_ffn_wq with R = T*k.
- * moe_grouped_ffn_wq_gated_supported returns 1 when a call with these sizes is taken: fp16
- * activations, per-channel scales, T*k <= 256, and d such that fc1 runs in the straight-line
- * streaming kernel (d = 1024 or 2048 with 4-bit, 512 or 1024 with 8-bit weights) under the
- * row bound T.  Otherwise the call returns MOE_ERR_UNSUPPORTED and nothing is launched.
+ *   expert_scale [T*k] fp32 or NULL.  When given, moe_combine is fused in as well: y_perm is
+ *   then the layer output out [T,d], fp32 (y_dtype must be MOE_F32): fc1 clears it and fc2 adds
+ *   expert_scale[a] * y[row of a] into row a / k with hardware fp32 adds.  A token gets at
+ *   most two terms and fp32 addition of two terms onto zero is commutative, so the result
+ *   does not depend on the order of arrival; rows of pruned tokens stay zero.
+ * moe_grouped_ffn_wq_gated_supported returns 0 when a call with these sizes is not taken
+ * (it then returns MOE_ERR_UNSUPPORTED and launches nothing), 1 when it is taken with
+ * expert_scale = NULL, 2 when expert_scale may be given too.  Taken: fp16 activations,
+ * per-channel scales, T*k <= 256, and d such that fc1 runs in the straight-line streaming
+ * kernel (d = 1024 or 2048 with 4-bit, 512 or 1024 with 8-bit weights) under the row bound T;
+ * for 2, F at most 4096 (4-bit) or 2048 (8-bit) and a multiple of 1024 / 512 as well.
  */
 int moe_grouped_ffn_wq_gated_supported(int T, int k, int E, int d, int F, int bits, int group_size,
                                        int act_dtype);
-int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx, int T, int k,
+int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx,
+                             const float *expert_scale, int T, int k,
                              int E, int d, int F, int bits, int group_size, int activation,
                              const void *w1_packed, const void *s1, const void *b1,
                              const void *w2_packed, const void *s2, const void *b2, void *y_perm,

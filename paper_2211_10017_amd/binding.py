@@ -65,7 +65,7 @@ def load():
     lib.moe_grouped_ffn_wq_gated_supported.restype = i
     lib.moe_grouped_ffn_wq_gated_supported.argtypes = [i, i, i, i, i, i, i, i]
     lib.moe_grouped_ffn_wq_gated.restype = i
-    lib.moe_grouped_ffn_wq_gated.argtypes = [vp, i, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, vp,
+    lib.moe_grouped_ffn_wq_gated.argtypes = [vp, i, vp, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, vp, vp,
                                              vp, sz, vp]
     lib.moe_pack_fp16_experts.restype = i
     lib.moe_pack_fp16_experts.argtypes = [vp, i, i, i, vp, vp]
@@ -255,24 +255,31 @@ def moe_grouped_ffn_wq_routed(x, perm_src, k: int, expert_offsets, E: int, d: in
     return out
 
 
-def moe_grouped_ffn_wq_gated_supported(T: int, k: int, E: int, d: int, F: int, bits: int, group_size: int, act_dtype) -> bool:
-    return bool(load().moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, _DT[act_dtype]))
+def moe_grouped_ffn_wq_gated_supported(T: int, k: int, E: int, d: int, F: int, bits: int, group_size: int, act_dtype) -> int:
+    """0: not taken; 1: permute + FFN; 2: expert_scale may be given as well (combine fused in)."""
+    return int(load().moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, _DT[act_dtype]))
 
 
 def moe_grouped_ffn_wq_gated(x, expert_idx, E: int, d: int, F: int, bits: int, group_size: int, w1_packed, s1, w2_packed,
-                             s2, b1=None, b2=None, y_dtype=None, workspace=None, activation: str = "relu"):
-    """Decode-sized batches: permute + FFN in one call.  Returns (y_perm, perm_src, inv_perm, expert_offsets)."""
+                             s2, b1=None, b2=None, y_dtype=None, workspace=None, activation: str = "relu",
+                             expert_scale=None):
+    """Decode-sized batches: permute + FFN (+ combine when expert_scale is given) in one call.
+    Returns (y_perm [R,d] or, with expert_scale, out [T,d] fp32, perm_src, inv_perm, expert_offsets)."""
     T, k = expert_idx.shape
     R = T * k
     dev = x.device
-    y = torch.empty((R, d), dtype=y_dtype or x.dtype, device=dev)
+    if expert_scale is not None:
+        y = torch.empty((T, d), dtype=torch.float32, device=dev)
+    else:
+        y = torch.empty((R, d), dtype=y_dtype or x.dtype, device=dev)
     perm_src = torch.empty(R, dtype=torch.int32, device=dev)
     inv_perm = torch.empty(R, dtype=torch.int32, device=dev)
     offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
     if workspace is None:
         workspace = torch.empty(moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, x.dtype), dtype=torch.uint8, device=dev)
     rc = load().moe_grouped_ffn_wq_gated(
-        _ptr(x, torch.float16, "x"), _DT[x.dtype], _ptr(expert_idx, torch.int32, "expert_idx"), T, k, E, d, F, bits,
+        _ptr(x, torch.float16, "x"), _DT[x.dtype], _ptr(expert_idx, torch.int32, "expert_idx"),
+        _ptr(expert_scale, torch.float32, "expert_scale"), T, k, E, d, F, bits,
         group_size, ACTIVATIONS[activation], _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"),
         _ptr(b1, torch.float16, "b1"), _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"),
         _ptr(b2, torch.float16, "b2"), _ptr(y), _DT[y.dtype], _ptr(perm_src), _ptr(inv_perm), _ptr(offsets),

@@ -81,10 +81,10 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     if (stream_ok && (max_rows <= 64 || few)) {
         g.row_hi = 0x7fffffff;                 // every expert streams, `fit` rows per block
         if (unrolled) return launch_stream_unrolled(g, bits, max_rows, s);
-        if (g.gate_idx) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel", g.K);
+        if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel", g.K);
         return launch_stream_gemm(g, bits, smode, max_rows, s);
     }
-    if (g.gate_idx) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: these sizes do not run in the straight-line kernel");
+    if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: these sizes do not run in the straight-line kernel");
     if (stream_ok && mean <= 96) {
         g.row_hi = fit;
         int rc = launch_stream_gemm(g, bits, smode, max_rows, s);
@@ -161,6 +161,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     if (gate_idx) {     // decode-sized: fc1 rebuilds the permutation from the gate's output and writes the index arrays
         g1.gate_idx = gate_idx; g1.n_assign = R; g1.gate_k = k;
         g1.perm_src_out = perm_src_out; g1.inv_perm_out = inv_perm_out; g1.offsets_out = offsets_out;
+        if (expert_scale) { g1.zero_out = (float *)y_perm; g1.zero_count = (long)(R / k) * d; }   // fc2 adds into it
     }
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, R, d, pow_x);
@@ -179,8 +180,12 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     g2.out = y_perm; g2.K = F; g2.N = d; g2.g = grouped ? group_size : F;
     g2.out_dtype = y_dtype; g2.act = MOE_ACT_NONE;
     g2.a_src = nullptr;
-    g2.gate_idx = nullptr;
-    if (expert_scale) { g2.out_dst = perm_src; g2.out_scale = expert_scale; }
+    g2.gate_idx = nullptr; g2.zero_out = nullptr;
+    if (gate_idx && expert_scale) {     // un-permute fused into fc2: fc1 clears out, fc2 adds scale * y into the tokens' rows
+        g2.out_dst = perm_src_out; g2.out_scale = expert_scale; g2.out_add = 1; g2.out_div = k;
+    } else if (expert_scale) {
+        g2.out_dst = perm_src; g2.out_scale = expert_scale;
+    }
     if (bf) {
         hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)h, R, F, pow_h);
         rc = check_launch("moe_grouped_ffn_wq (row scale h)");
@@ -236,25 +241,29 @@ extern "C" int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int
 // streaming kernel, whose blocks rebuild the permutation from the gate's expert indices, fetch their
 // rows from the tokens and write perm_src / inv_perm / expert_offsets on the way; fc2 and moe_combine
 // then read those arrays as after moe_permute.
-static bool gated_shapes(int T, int k, int E, int d, int F, int bits, int group_size, int act_dtype)
+static int gated_shapes(int T, int k, int E, int d, int F, int bits, int group_size, int act_dtype)
 {
     using namespace moe;
-    if (T <= 0 || k < 1 || k > 2 || E <= 0 || d <= 0 || F <= 0 || act_dtype != MOE_F16) return false;
-    if ((long)T * k > kGatedMaxAssign || (bits != 4 && bits != 8) || d % 64 || F % 64) return false;
-    if (group_size != 0 && !(group_size == d && group_size == F)) return false;
-    if (!stream_unrolled_supports(d, bits, SCALE_CHANNEL) || !stream_unrolled_takes_gate(d, bits)) return false;
+    if (T <= 0 || k < 1 || k > 2 || E <= 0 || d <= 0 || F <= 0 || act_dtype != MOE_F16) return 0;
+    if ((long)T * k > kGatedMaxAssign || (bits != 4 && bits != 8) || d % 64 || F % 64) return 0;
+    if (group_size != 0 && !(group_size == d && group_size == F)) return 0;
+    if (!stream_unrolled_supports(d, bits, SCALE_CHANNEL) || !stream_unrolled_takes_gate(d, bits)) return 0;
     // the dispatch rule of run_gemm must send fc1 to the straight-line kernel alone (row bound T)
     const int R = T * k, mean = (R + E - 1) / E;
-    return T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(d, T));
+    if (!(T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(d, T)))) return 0;
+    // ... and fc2 as well, if it is to add its rows straight into the layer output
+    const bool fc2 = stream_unrolled_supports(F, bits, SCALE_CHANNEL) && (T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(F, T)));
+    return fc2 ? 2 : 1;
 }
 
 extern "C" int moe_grouped_ffn_wq_gated_supported(int T, int k, int E, int d, int F, int bits, int group_size,
                                                   int act_dtype)
 {
-    return gated_shapes(T, k, E, d, F, bits, group_size, act_dtype) ? 1 : 0;
+    return gated_shapes(T, k, E, d, F, bits, group_size, act_dtype);
 }
 
-extern "C" int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx, int T, int k,
+extern "C" int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int32_t *expert_idx,
+                                        const float *expert_scale, int T, int k,
                                         int E, int d, int F, int bits, int group_size, int activation,
                                         const void *w1_packed, const void *s1, const void *b1,
                                         const void *w2_packed, const void *s2, const void *b2, void *y_perm,
@@ -265,11 +274,15 @@ extern "C" int moe_grouped_ffn_wq_gated(const void *x, int act_dtype, const int3
     using namespace moe;
     if (!expert_idx || !perm_src || !inv_perm || !expert_offsets)
         return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq_gated: NULL pointer");
-    if (!gated_shapes(T, k, E, d, F, bits, group_size, act_dtype))
+    const int level = gated_shapes(T, k, E, d, F, bits, group_size, act_dtype);
+    if (!level)
         return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: only decode-sized fp16 batches with per-channel scales "
                                          "(T*k <= %d) are taken: use moe_permute + moe_grouped_ffn_wq", kGatedMaxAssign);
+    if (expert_scale && (level < 2 || y_dtype != MOE_F32))
+        return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: the fused un-permute needs an fp32 output and an fc2 that runs "
+                                         "in the straight-line streaming kernel: pass expert_scale = NULL and use moe_combine");
     return ffn_impl(x, act_dtype, expert_offsets, T * k, E, T, d, F, bits, group_size, activation, w1_packed, s1, b1,
-                    w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, k, nullptr,
+                    w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, k, expert_scale,
                     expert_idx, perm_src, inv_perm, expert_offsets);
 }
 

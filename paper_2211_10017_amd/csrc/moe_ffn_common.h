@@ -36,6 +36,13 @@ struct GemmArgs {
     const int32_t *gate_idx;  // [n_assign] or null
     int n_assign, gate_k;
     int32_t *perm_src_out, *inv_perm_out, *offsets_out;
+    float *zero_out;          // or null: fp32 buffer the launch clears (zero_count floats, a multiple of 4) for the
+    long zero_count;          // launch after it, which adds rows into it
+    // straight-line streaming kernel, fused un-permute for k <= 2: with out_add set, row r of the result,
+    // times out_scale[a], a = out_dst[r], is ADDED to row a / out_div of the fp32 buffer `out` (cleared
+    // before).  A token's at most two terms arrive in either order; fp32 addition of two terms onto
+    // zero is commutative, so the sum does not depend on it.
+    int out_add, out_div;
 };
 
 constexpr int kGatedMaxAssign = 256;    // assignments the fused permutation takes: one per thread of a block

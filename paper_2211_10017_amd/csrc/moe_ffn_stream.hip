@@ -191,6 +191,13 @@ constexpr int kUnrolledFitCap = 16;    // rows per block: 16 rows of K = 1024 le
 // vectors one thread stages for a K extent: all of kUnrolledFitCap rows, but no more than kStageVecs
 __host__ __device__ constexpr int stage_vecs(int K) { return kUnrolledFitCap * (K / 8) / 256 < kStageVecs ? kUnrolledFitCap * (K / 8) / 256 : kStageVecs; }
 
+// out[a / out_div][n] += out_scale[a] * v for permuted row r, a = out_dst[r] (hardware fp32 add, no return value)
+__device__ inline void add_to_token(const GemmArgs &p, int r, int n, float v)
+{
+    const int a = p.out_dst[r];
+    unsafeAtomicAdd(reinterpret_cast<float *>(p.out) + (size_t)(a / p.out_div) * p.N + n, v * p.out_scale[a]);
+}
+
 //
 // KS = 4 splits the K range of a slab over the four wavefronts of the block (a slab of 64 blocks
 // would otherwise be one long, latency-bound stream per wavefront while most of the chip idles):
@@ -228,6 +235,12 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     __shared__ int s_cnt[3][4];                 // per wavefront: assignments of this expert, of earlier experts, pruned
     __shared__ int s_tok[kUnrolledFitCap];      // token of each row of this block
     if constexpr (PERM) {
+        if (p.zero_out) {                       // every block clears its share of the buffer the next launch adds into
+            const long nblk = (long)gridDim.x * gridDim.y * gridDim.z;
+            const long blk = ((long)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+            float4 *z4 = reinterpret_cast<float4 *>(p.zero_out);
+            for (long i = blk * 256 + threadIdx.x; i < p.zero_count / 4; i += nblk * 256) z4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
         const int a = threadIdx.x;
         const int v = a < p.n_assign ? p.gate_idx[a] : 0x7fffffff;
         const bool mine = v == e, before = v < e, pruned = v == p.E;
@@ -324,6 +337,18 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
     __syncthreads();
     if (!has) return;
 
+    // fused un-permute (KS = 4): the destinations and gate scales of the four rows this lane will
+    // finish are fetched now, under the weight stream, not at the end of the kernel
+    int dst_tok[4];
+    float dst_scale[4];
+    if (KS == 4 && p.out_add) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int a = p.out_dst[lo + min(4 * (lane >> 5) + 8 * wave + i, rows - 1)];
+            dst_tok[i] = a / p.out_div;
+            dst_scale[i] = p.out_scale[a];
+        }
+    }
     const uint16_t *arow = lds_a + (size_t)min(lane & 31, rows - 1) * LDR + 8 * (lane >> 5) +
                            kq * KBW * FK;               // clamped to a live row
     float *part = reinterpret_cast<float *>(lds_a);    // KS = 4: [slab][wave][16][64] partial tiles, over the rows once they are used up
@@ -385,7 +410,14 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
                         o += (q & 3) == 3 ? (size_t)5 * N : (size_t)N;
                     }
                 };
-                if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
+                if (p.out_add) {                        // fused un-permute: scaled rows added to their tokens' rows
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const int r = rbase + 8 * (q >> 2) + (q & 3);
+                        if (r < rows) add_to_token(p, lo + r, n, v[q]);
+                    }
+                }
+                else if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
                 else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
                 else put(reinterpret_cast<uint16_t *>(out_rows));
             } else if constexpr (sl == TPW - 1) {
@@ -420,7 +452,13 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
                             o += N;
                         }
                     };
-                    if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
+                    if (p.out_add) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (rbase + 8 * wave + i < rows)
+                                unsafeAtomicAdd(reinterpret_cast<float *>(p.out) + (size_t)dst_tok[i] * N + na, v[i] * dst_scale[i]);
+                    }
+                    else if (p.out_dtype == MOE_F16) put(reinterpret_cast<_Float16 *>(out_rows));
                     else if (p.out_dtype == MOE_F32) put(reinterpret_cast<float *>(out_rows));
                     else put(reinterpret_cast<uint16_t *>(out_rows));
                 }

@@ -47,7 +47,7 @@ class MoEExpertLayer:
         # the GEMMs instead of as copies of their own
         self.routed = bool(fuse_routing) and B.moe_grouped_ffn_wq_routed_supported(R, E, T, d, F, bits, group_size, act_dtype)
         # decode-sized batches: the permutation is rebuilt inside fc1 (no permute launch, no x_perm copy)
-        self.gated = bool(fuse_routing) and B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, act_dtype)
+        self.gated = B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, group_size, act_dtype) if fuse_routing else 0
 
     # -- offline: quantise one expert matrix from its fp32 master (which = 1 | 2) ------------
     def load_expert(self, which: int, e: int, w_fp32, q_canon_out=None):
@@ -126,12 +126,15 @@ class MoEExpertLayer:
         combine = (lib.moe_combine, (p(self.y_perm), ydt, p(self.inv_perm), p(self.expert_scale), active, self.T, self.k,
                                      self.d, p(self.out), odt, st), "moe_combine")
         if self.gated:
+            # level 2 with an fp32 layer output: fc2 adds the scaled rows straight into out (no combine launch)
+            fused = self.gated == 2 and self.out_dtype == torch.float32
             ffn = (lib.moe_grouped_ffn_wq_gated,
-                   (p(x), dt, p(self.expert_idx), self.T, self.k, self.E, self.d, self.F, self.bits, self.group_size,
-                    self.activation, p(self.w1_packed), p(self.s1), p(self.b1), p(self.w2_packed), p(self.s2), p(self.b2),
-                    p(self.y_perm), ydt, p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_ffn),
+                   (p(x), dt, p(self.expert_idx), p(self.expert_scale) if fused else None, self.T, self.k, self.E, self.d,
+                    self.F, self.bits, self.group_size, self.activation, p(self.w1_packed), p(self.s1), p(self.b1),
+                    p(self.w2_packed), p(self.s2), p(self.b2), p(self.out) if fused else p(self.y_perm),
+                    odt if fused else ydt, p(self.perm_src), p(self.inv_perm), p(self.expert_offsets), p(self.ws_ffn),
                     self.ws_ffn.numel(), st), "moe_grouped_ffn_wq_gated")
-            return [gate, ffn, combine]
+            return [gate, ffn] if fused else [gate, ffn, combine]
         if self.routed:
             # index only (no x_perm copy); fc1 gathers, and fc2 scatters when there is one expert per
             # token and no pruned row (a pruned token's output row would stay unwritten)

@@ -14,6 +14,11 @@ from helpers import MAX_ABS_TOL, REL_L2_TOL, Prepared, error_metrics, oracle_dty
 from paper_2211_10017_amd import binding as B
 from paper_2211_10017_amd import workloads as W
 
+
+def _adds_into_out(layer) -> bool:
+    """Decode-sized layers whose fc2 adds the scaled fp32 rows straight into the output: y is never rounded."""
+    return layer.gated == 2 and layer.out_dtype == torch.float32
+
 pytestmark = pytest.mark.gpu
 
 
@@ -50,7 +55,7 @@ def _check_layer(prep, sample_tokens):
     else:
         tokens = np.random.default_rng(w.seed).choice(w.T, size=sample_tokens, replace=False)
     # with one expert per token a routed layer scales and stores fc2's fp32 result directly: y is never rounded
-    y_dt = torch.float32 if (layer.routed and w.k == 1) else layer.y_dtype
+    y_dt = torch.float32 if (layer.routed and w.k == 1) or _adds_into_out(layer) else layer.y_dtype
     tokens, want = prep.oracle_out_for_tokens(tokens, idx, scale, perm_src, inv_perm, off, oracle_dtype_code(y_dt))
     max_abs, rel = error_metrics(got[tokens], want)
     _say(f"   {w.name}: tokens checked {len(tokens)}  max_abs={max_abs:.3e}  rel_l2={rel:.3e}")
@@ -82,7 +87,7 @@ def test_config_with_pruned_rows(name):
     fin = (np.random.default_rng(w.seed + 100).random(w.T) < 0.4).astype(np.uint8)
     res = oracle.moe_layer(prep.x, prep.wg, prep.bias, prep.q[1], prep.s[1], prep.q[2], prep.s[2], w.k,
                            w.group_size, oracle_dtype_code(layer.act_dtype), renormalize=w.renormalize,
-                           y_dtype=oracle_dtype_code(layer.y_dtype), finished=fin)
+                           y_dtype=oracle_dtype_code(torch.float32 if _adds_into_out(layer) else layer.y_dtype), finished=fin)
     out = layer.forward(prep.x_dev, finished=to_dev(fin, torch.uint8))
     torch.cuda.synchronize()
     assert np.array_equal(layer.expert_idx.cpu().numpy(), res["expert_idx"])

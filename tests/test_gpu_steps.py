@@ -383,8 +383,9 @@ def test_gated_ffn_matches_oracle(T, k, E, d, F, bits, prune):
     _, ds1, p1 = B.moe_quantize_experts(to_dev(w1, torch.float32), bits, 0, want_canon=False)
     _, ds2, p2 = B.moe_quantize_experts(to_dev(w2, torch.float32), bits, 0, want_canon=False)
     xd = to_dev(x, torch.float16)
-    assert B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, 0, torch.float16)
-    idx, _ = B.moe_gate_topk(xd, to_dev(wg, torch.float16), None, k, True, finished=to_dev(finished, torch.uint8) if prune else None)
+    level = B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, 0, torch.float16)
+    assert level >= 1
+    idx, scale = B.moe_gate_topk(xd, to_dev(wg, torch.float16), None, k, True, finished=to_dev(finished, torch.uint8) if prune else None)
     assert np.array_equal(idx.cpu().numpy(), idx_o)
     y, ps, ip, of = B.moe_grouped_ffn_wq_gated(xd, idx, E, d, F, bits, 0, p1, ds1, p2, ds2, y_dtype=torch.float32)
     torch.cuda.synchronize()
@@ -393,6 +394,19 @@ def test_gated_ffn_matches_oracle(T, k, E, d, F, bits, prune):
     max_abs, rel = error_metrics(y.cpu().numpy()[:active], y_o)
     _say(f"   active rows {active} of {T * k}; max_abs={max_abs:.3e} rel_l2={rel:.3e}")
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+    if level == 2:      # un-permute fused in as well: fc2 adds the scaled rows into the layer output
+        y_full = np.zeros((T * k, d), dtype=np.float32)
+        y_full[:active] = y_o
+        out_o = oracle.combine(y_full, inv_perm_o, scale.cpu().numpy(), T, k, active_rows=active)
+        out1 = B.moe_grouped_ffn_wq_gated(xd, idx, E, d, F, bits, 0, p1, ds1, p2, ds2, expert_scale=scale)[0]
+        out2 = B.moe_grouped_ffn_wq_gated(xd, idx, E, d, F, bits, 0, p1, ds1, p2, ds2, expert_scale=scale)[0]
+        torch.cuda.synchronize()
+        got = out1.cpu().numpy()
+        assert np.array_equal(got, out2.cpu().numpy())               # the order of a token's two terms does not show
+        assert not got[finished == 1].any()                          # pruned tokens: exactly zero
+        max_abs, rel = error_metrics(got, out_o)
+        _say(f"   un-permute fused: max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+        assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
 
 def test_gated_ffn_refuses_other_sizes():
@@ -401,7 +415,8 @@ def test_gated_ffn_refuses_other_sizes():
     assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 128, torch.float16)    # group scales
     assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, torch.bfloat16)     # bf16 rows
     assert not B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 4096, 4096, 4, 0, torch.float16)      # fc1 slabs of 64 blocks
-    assert B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, torch.float16)
+    assert B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, torch.float16) == 2
+    assert B.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 8192, 4, 0, torch.float16) == 1   # fc2's slabs too long for the fused un-permute
 
 
 def test_routed_ffn_refuses_decode_sizes():
