@@ -62,6 +62,40 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.moe_combine(fake, 5, fake, fake, None, 4, 1, 64, fake, 2, None) == 2
 
 
+def test_fused_entry_points_say_on_the_host_what_they_take(lib):
+    F16, BF16 = binding.MOE_F16, binding.MOE_BF16
+    # routing fused into the tiled GEMMs: only sizes that run entirely in the tiled kernel, fp16 rows
+    assert lib.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, F16) == 1
+    assert lib.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, BF16) == 0
+    assert lib.moe_grouped_ffn_wq_routed_supported(128, 32, 64, 1024, 4096, 4, 0, F16) == 0
+    # permutation rebuilt inside fc1: decode sizes only; 2 = the un-permute may be fused in as well
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, F16) == 2        # the decode workload
+    assert lib.moe_grouped_ffn_wq_gated_supported(256, 1, 8, 512, 2048, 8, 0, F16) == 2         # 256 assignments: the most
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 8192, 4, 0, F16) == 1        # fc2's slabs too long to add into out
+    assert lib.moe_grouped_ffn_wq_gated_supported(129, 2, 32, 1024, 4096, 4, 0, F16) == 0       # 258 assignments
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 128, F16) == 0      # group scales
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, BF16) == 0       # bf16 rows
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 4096, 4096, 4, 0, F16) == 0        # fc1's slabs too long
+    assert lib.moe_grouped_ffn_wq_gated_supported(64, 3, 32, 1024, 4096, 4, 0, F16) == 0        # k = 3
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)          # never dereferenced: validation fails first
+    gated = lib.moe_grouped_ffn_wq_gated
+    assert gated(fake, 0, None, None, 64, 2, 32, 1024, 4096, 4, 0, 0, fake, fake, None, fake, fake, None, fake, 0,
+                 fake, fake, fake, fake, 1 << 30, None) == 1                                     # no expert_idx
+    assert gated(fake, 0, fake, None, 512, 1, 8, 1024, 4096, 4, 0, 0, fake, fake, None, fake, fake, None, fake, 0,
+                 fake, fake, fake, fake, 1 << 30, None) == 2                                     # too many assignments
+    assert b"decode-sized" in lib.moe_last_error()
+    assert gated(fake, 0, fake, fake, 64, 2, 32, 1024, 4096, 4, 0, 0, fake, fake, None, fake, fake, None, fake, 0,
+                 fake, fake, fake, fake, 1 << 30, None) == 2                                     # fused un-permute needs an fp32 output
+    assert gated(fake, 0, fake, None, 64, 2, 32, 1024, 4096, 4, 0, 0, fake, fake, None, fake, fake, None, fake, 0,
+                 fake, fake, fake, fake, 16, None) == 3                                          # workspace too small
+    routed = lib.moe_grouped_ffn_wq_routed
+    assert routed(fake, 0, fake, 2, fake, fake, 16384, 64, 8192, 4096, 16384, 4, 128, 0, fake, fake, None, fake, fake, None,
+                  fake, 2, fake, 1 << 40, None) == 1                                             # fused un-permute needs k = 1
+    assert routed(fake, 0, fake, 1, None, fake, 128, 32, 64, 1024, 4096, 4, 0, 0, fake, fake, None, fake, fake, None,
+                  fake, 0, fake, 1 << 30, None) == 2                                             # decode sizes are not taken
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
