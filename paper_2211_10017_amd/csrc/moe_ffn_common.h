@@ -24,6 +24,7 @@ struct GemmArgs {
     int out_dtype;
     int act;                  // MOE_ACT_NONE (plain GEMM) | MOE_ACT_RELU | MOE_ACT_GELU applied after the bias
     int row_lo;               // tiled kernel: only experts with more than row_lo rows
+    int tile_units;           // tiled kernel: row tiles of at most 32 * tile_units rows (set by the launcher)
     int row_hi;               // streaming kernel: only experts with 1..row_hi rows
     // tiled kernel only: rows fetched / stored through the routing index instead of a permuted copy
     const int32_t *a_src;     // [R] or null: row r of A is a[a_src[r] / a_div]

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: tile addresses stay scalar
     const int K = p.K, N = p.N;
     int e, col, row0, rows;
-    if (!find_item(p.offsets, p.E, p.R, BM, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
+    if (!find_item(p.offsets, p.E, p.R, 32 * p.tile_units, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
     e = __builtin_amdgcn_readfirstlane(e), col = __builtin_amdgcn_readfirstlane(col);      // the same in every lane: kept in scalar registers
     row0 = __builtin_amdgcn_readfirstlane(row0), rows = __builtin_amdgcn_readfirstlane(rows);
 
@@ -389,16 +389,30 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
     const int mean = (p.R + p.E - 1) / p.E;
     int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
     if (smode == SCALE_GROUP_ACC && tm > 2) tm = 2;
-    const int bm = 32 * tm;
     const long most = (long)p.R / (p.row_lo + 1);               // experts that can exceed row_lo rows
-    const long slots = (long)p.R / bm + (p.E < most ? p.E : most);
-    if (slots == 0) return MOE_OK;
     const long ncol = (p.N + 255) / 256;
+    // Tiles may be lower than the kernel's 32 * tm rows (it skips row tiles that hold no rows): with few
+    // column blocks the launch is a handful of rounds of 512 blocks (two per CU), and 96-row tiles
+    // can fill the last round better than 128-row tiles leave it.  Cost model: rounds x tile height,
+    // lower tiles charged 6 % per step down for streaming the weights more often.
+    int units = tm;
+    if (tm == 4) {
+        double best = 0;
+        for (int u = 4; u >= 2; --u) {
+            const long items = ((long)p.R / (32 * u) + (p.E < most ? p.E : most) / 2) * ncol;
+            const double cost = (double)((items + 511) / 512) * u * (1.0 + 0.06 * (4 - u));
+            if (u == 4 || cost < best) { best = cost; units = u; }
+        }
+    }
+    GemmArgs q = p;
+    q.tile_units = units;
+    const long slots = (long)p.R / (32 * units) + (p.E < most ? p.E : most);
+    if (slots == 0) return MOE_OK;
     const long wgs = (slots * ncol + kXcds - 1) / kXcds * kXcds;   // upper bound of the work items, whole rounds of XCDs
     if (wgs > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: %ld workgroups exceed one launch", wgs);
     dim3 grid((unsigned)wgs);
-    if (bits == 4) launch_mode<4>(p, smode, abf16, tm, grid, s);
-    else launch_mode<8>(p, smode, abf16, tm, grid, s);
+    if (bits == 4) launch_mode<4>(q, smode, abf16, tm, grid, s);
+    else launch_mode<8>(q, smode, abf16, tm, grid, s);
     return check_launch("moe_grouped_ffn_wq (gemm)");
 }
 
