@@ -8,6 +8,8 @@
 // launch shape.  Softmax and top-k are butterfly reductions over the EL lanes of a group.
 #include <math.h>
 
+#include <type_traits>
+
 #include "moe_common.h"
 
 namespace moe {
@@ -30,6 +32,45 @@ __device__ inline float mac(uint16_t xb, uint16_t wb, float acc)
 {
     if (BF16) return fmaf(__uint_as_float((uint32_t)xb << 16), __uint_as_float((uint32_t)wb << 16), acc);
     return fmaf((float)__builtin_bit_cast(_Float16, xb), (float)__builtin_bit_cast(_Float16, wb), acc);
+}
+
+// Value of the partner lane of butterfly step `off` within a lane group.  Steps 1 and 2 are quad
+// permutes, 4 and 8 the half-row and row mirrors (the same partner sets once the value is uniform
+// over 4 resp. 8 lanes, which the earlier steps have made it), all in the VALU's data-parallel
+// primitives, the steps across 16-lane rows and 32-lane halves the row and half swaps.  Used in ascending
+// order of `off` by reductions whose operation is commutative.
+template <int OFF, typename V>
+__device__ inline V butterfly_partner(V v)
+{
+    const int b = __builtin_bit_cast(int, v);
+    int r;
+    if (OFF == 1) r = __builtin_amdgcn_update_dpp(0, b, 0xB1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+    else if (OFF == 2) r = __builtin_amdgcn_update_dpp(0, b, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+    else if (OFF == 4) r = __builtin_amdgcn_update_dpp(0, b, 0x141, 0xf, 0xf, false);  // row_half_mirror
+    else if (OFF == 8) r = __builtin_amdgcn_update_dpp(0, b, 0x140, 0xf, 0xf, false);  // row_mirror
+    else if (OFF == 16) {
+        // rows of 16 lanes: the swap leaves [r0, r0, r2, r2] and [r1, r1, r3, r3]; a lane in an even row
+        // takes the second, a lane in an odd row the first
+        const auto sw = __builtin_amdgcn_permlane16_swap((unsigned)b, (unsigned)b, false, false);
+        r = (int)((threadIdx.x & 16) ? sw[0] : sw[1]);
+    } else {
+        // halves of 32 lanes: the swap leaves [lo, lo] and [hi, hi]
+        const auto sw = __builtin_amdgcn_permlane32_swap((unsigned)b, (unsigned)b, false, false);
+        r = (int)((threadIdx.x & 32) ? sw[0] : sw[1]);
+    }
+    return __builtin_bit_cast(V, r);
+}
+
+// f(partner value getter) for every butterfly step of a group of EL lanes (EL = 8, 16, 32 or 64)
+template <typename F>
+__device__ inline void butterfly_steps(int EL, F &&f)
+{
+    f(std::integral_constant<int, 1>{});
+    f(std::integral_constant<int, 2>{});
+    f(std::integral_constant<int, 4>{});
+    if (EL > 8) f(std::integral_constant<int, 8>{});
+    if (EL > 16) f(std::integral_constant<int, 16>{});
+    if (EL > 32) f(std::integral_constant<int, 32>{});
 }
 
 // With E <= 64 the 128 x E block of the gate weight that a wavefront needs per turn is copied
@@ -233,11 +274,12 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
             const bool taken = j == 1 && e == sel[0];
             if (e < E && !taken && (lg[a] > bv || be == 0x7fffffff)) { bv = lg[a]; be = e; }
         }
-        for (int off = EL >> 1; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oe = __shfl_xor(be, off);
+        butterfly_steps(EL, [&](auto off) {
+            constexpr int OFF = decltype(off)::value;
+            const float ov = butterfly_partner<OFF>(bv);
+            const int oe = butterfly_partner<OFF>(be);
             if (oe != 0x7fffffff && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be))) { bv = ov; be = oe; }
-        }
+        });
         sel[j] = be;
         selv[j] = bv;
     }
@@ -246,7 +288,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 #pragma unroll
     for (int a = 0; a < NE; ++a)
         if (a * 64 + le < E) den += expf(lg[a] - lmax);
-    for (int off = EL >> 1; off > 0; off >>= 1) den += __shfl_xor(den, off);
+    butterfly_steps(EL, [&](auto off) { den += butterfly_partner<decltype(off)::value>(den); });
 
     if (le == 0 && t < T) {
         if (finished && finished[t]) {
