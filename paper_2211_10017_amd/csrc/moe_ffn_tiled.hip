@@ -322,39 +322,59 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     else k_loop(std::integral_constant<int, 1>{});
     if constexpr (DMA) wait_loads<0>();      // the last step's (unused) refill of the other stage must land before the block's LDS is given up
 
-    // ---- epilogue: scale (per channel), bias, ReLU, store.  acc[m][t][i] is row
+    // ---- epilogue: scale (per channel), bias, activation, store.  acc[m][t][i] is row
     // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
+    // 16-bit outputs leave in 4-byte stores: registers i and i+1 are two rows of one channel; a lane
+    // hands the row its neighbour (lane ^ 1, the next channel) keeps to that neighbour and gets the
+    // other row's value back, so the even lane stores channels (n, n+1) of the first row and the
+    // odd lane channels (n-1, n) of the second.
+    auto finish = [&](float a, int rl, float cs, float bias) {
+        float v = a * cs;
+        if (ABF16) v *= p.row_pow[row0 + min(rl, rows - 1)].y;
+        v += bias;
+        v = activate(v, p.act);
+        if (p.out_dst) v *= s_scale[min(rl, rows - 1)];         // gate scale of the fused un-permute
+        return v;
+    };
+    auto store_tiles = [&](auto out_tag) {
+        using OT = decltype(out_tag);                            // float | _Float16 | uint16_t (bf16 bits)
+        OT *out = reinterpret_cast<OT *>(p.out);
 #pragma unroll
-    for (int t = 0; t < kTN; ++t) {
-        if (!tile_ok[t]) continue;
-        const int n = (ntile0 + t) * 32 + (lane & 31);
-        float cs = 1.0f;
-        if (SMODE == SCALE_CHANNEL) cs = __half2float(p.scales[(size_t)e * N + n]);
-        if (SMODE == SCALE_GROUP_SPLIT) cs = 1.0f / 256.0f;
-        const float bias = p.bias ? __half2float(p.bias[(size_t)e * N + n]) : 0.0f;
+        for (int t = 0; t < kTN; ++t) {
+            if (!tile_ok[t]) continue;
+            const int n = (ntile0 + t) * 32 + (lane & 31);
+            float cs = 1.0f;
+            if (SMODE == SCALE_CHANNEL) cs = __half2float(p.scales[(size_t)e * N + n]);
+            if (SMODE == SCALE_GROUP_SPLIT) cs = 1.0f / 256.0f;
+            const float bias = p.bias ? __half2float(p.bias[(size_t)e * N + n]) : 0.0f;
 #pragma unroll
-        for (int m = 0; m < TM; ++m) {
+            for (int m = 0; m < TM; ++m) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                if (rl >= rows) continue;
-                const int r = row0 + rl;
-                float v = acc[m][t][i] * cs;
-                if (ABF16) v *= p.row_pow[r].y;
-                v += bias;
-                v = activate(v, p.act);
-                int ro = r;
-                if (p.out_dst) {                                 // un-permute and gate scale fused into the store
-                    ro = s_dst[rl];
-                    v *= s_scale[rl];
+                for (int i = 0; i < 16; i += 2) {
+                    const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);     // row of register i; i + 1 is the next row
+                    const float v0 = finish(acc[m][t][i], rl, cs, bias), v1 = finish(acc[m][t][i + 1], rl + 1, cs, bias);
+                    if constexpr (std::is_same<OT, float>::value) {
+                        if (rl < rows) out[(size_t)(p.out_dst ? s_dst[rl] : row0 + rl) * N + n] = v0;
+                        if (rl + 1 < rows) out[(size_t)(p.out_dst ? s_dst[rl + 1] : row0 + rl + 1) * N + n] = v1;
+                    } else {
+                        const bool odd = lane & 1;
+                        const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                                              0, __builtin_bit_cast(int, odd ? v0 : v1), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+                        const float lo = odd ? got : v0, hi = odd ? v1 : got;
+                        uint32_t packed;
+                        if constexpr (std::is_same<OT, _Float16>::value) packed = h2_bits(half2_t{(_Float16)lo, (_Float16)hi});
+                        else packed = (uint32_t)to_bf16_rne(lo) | ((uint32_t)to_bf16_rne(hi) << 16);
+                        const int rs = rl + (odd ? 1 : 0);
+                        if (rs < rows)
+                            *reinterpret_cast<uint32_t *>(out + (size_t)(p.out_dst ? s_dst[rs] : row0 + rs) * N + (n & ~1)) = packed;
+                    }
                 }
-                const size_t o = (size_t)ro * N + n;
-                if (p.out_dtype == MOE_F32) reinterpret_cast<float *>(p.out)[o] = v;
-                else if (p.out_dtype == MOE_BF16) reinterpret_cast<uint16_t *>(p.out)[o] = to_bf16_rne(v);
-                else reinterpret_cast<_Float16 *>(p.out)[o] = (_Float16)v;
             }
         }
-    }
+    };
+    if (p.out_dtype == MOE_F32) store_tiles(float{});
+    else if (p.out_dtype == MOE_BF16) store_tiles(uint16_t{});
+    else store_tiles(_Float16{});
 }
 
 template <int BITS, int SMODE, bool ABF16>
