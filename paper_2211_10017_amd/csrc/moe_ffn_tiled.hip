@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 
     // ---- epilogue: scale (per channel), bias, activation, store.  acc[m][t][i] is row
     // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
-    // 16-bit outputs leave in 4-byte stores: registers i and i+1 are two rows of one channel; a lane
+    // Two channels leave per store: registers i and i+1 are two rows of one channel; a lane
     // hands the row its neighbour (lane ^ 1, the next channel) keeps to that neighbour and gets the
     // other row's value back, so the even lane stores channels (n, n+1) of the first row and the
     // odd lane channels (n-1, n) of the second.
@@ -353,20 +353,19 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                 for (int i = 0; i < 16; i += 2) {
                     const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);     // row of register i; i + 1 is the next row
                     const float v0 = finish(acc[m][t][i], rl, cs, bias), v1 = finish(acc[m][t][i + 1], rl + 1, cs, bias);
-                    if constexpr (std::is_same<OT, float>::value) {
-                        if (rl < rows) out[(size_t)(p.out_dst ? s_dst[rl] : row0 + rl) * N + n] = v0;
-                        if (rl + 1 < rows) out[(size_t)(p.out_dst ? s_dst[rl + 1] : row0 + rl + 1) * N + n] = v1;
-                    } else {
-                        const bool odd = lane & 1;
-                        const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
-                                              0, __builtin_bit_cast(int, odd ? v0 : v1), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
-                        const float lo = odd ? got : v0, hi = odd ? v1 : got;
-                        uint32_t packed;
-                        if constexpr (std::is_same<OT, _Float16>::value) packed = h2_bits(half2_t{(_Float16)lo, (_Float16)hi});
-                        else packed = (uint32_t)to_bf16_rne(lo) | ((uint32_t)to_bf16_rne(hi) << 16);
-                        const int rs = rl + (odd ? 1 : 0);
-                        if (rs < rows)
-                            *reinterpret_cast<uint32_t *>(out + (size_t)(p.out_dst ? s_dst[rs] : row0 + rs) * N + (n & ~1)) = packed;
+                    const bool odd = lane & 1;
+                    const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
+                                          0, __builtin_bit_cast(int, odd ? v0 : v1), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+                    const float lo = odd ? got : v0, hi = odd ? v1 : got;
+                    const int rs = rl + (odd ? 1 : 0);
+                    if (rs < rows) {
+                        OT *dst = out + (size_t)(p.out_dst ? s_dst[rs] : row0 + rs) * N + (n & ~1);
+                        if constexpr (std::is_same<OT, float>::value)
+                            *reinterpret_cast<float2 *>(dst) = make_float2(lo, hi);
+                        else if constexpr (std::is_same<OT, _Float16>::value)
+                            *reinterpret_cast<uint32_t *>(dst) = h2_bits(half2_t{(_Float16)lo, (_Float16)hi});
+                        else
+                            *reinterpret_cast<uint32_t *>(dst) = (uint32_t)to_bf16_rne(lo) | ((uint32_t)to_bf16_rne(hi) << 16);
                     }
                 }
             }
