@@ -339,27 +339,33 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     auto store_tiles = [&](auto out_tag) {
         using OT = decltype(out_tag);                            // float | _Float16 | uint16_t (bf16 bits)
         OT *out = reinterpret_cast<OT *>(p.out);
+        // per-channel factors of the wavefront's two tiles first; then, row pair by row pair, both tiles:
+        // the two halves of a 128-byte line of the output leave back to back
+        float cs[kTN], bias[kTN];
 #pragma unroll
         for (int t = 0; t < kTN; ++t) {
-            if (!tile_ok[t]) continue;
-            const int n = (ntile0 + t) * 32 + (lane & 31);
-            float cs = 1.0f;
-            if (SMODE == SCALE_CHANNEL) cs = __half2float(p.scales[(size_t)e * N + n]);
-            if (SMODE == SCALE_GROUP_SPLIT) cs = 1.0f / 256.0f;
-            const float bias = p.bias ? __half2float(p.bias[(size_t)e * N + n]) : 0.0f;
+            const int n = (tile_ok[t] ? ntile0 + t : 0) * 32 + (lane & 31);       // clamped: always a channel of this expert
+            cs[t] = SMODE == SCALE_CHANNEL ? __half2float(p.scales[(size_t)e * N + n]) : SMODE == SCALE_GROUP_SPLIT ? 1.0f / 256.0f : 1.0f;
+            bias[t] = p.bias ? __half2float(p.bias[(size_t)e * N + n]) : 0.0f;
+        }
 #pragma unroll
-            for (int m = 0; m < TM; ++m) {
+        for (int m = 0; m < TM; ++m) {
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);     // row of register i; i + 1 is the next row
-                    const float v0 = finish(acc[m][t][i], rl, cs, bias), v1 = finish(acc[m][t][i + 1], rl + 1, cs, bias);
-                    const bool odd = lane & 1;
+            for (int i = 0; i < 16; i += 2) {
+                const int rl = 32 * m + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);     // row of register i; i + 1 is the next row
+                const bool odd = lane & 1;
+                const int rs = rl + (odd ? 1 : 0);
+                OT *dst_row = out + (size_t)(p.out_dst ? s_dst[min(rs, rows - 1)] : row0 + rs) * N;
+#pragma unroll
+                for (int t = 0; t < kTN; ++t) {
+                    if (!tile_ok[t]) continue;
+                    const int n = (ntile0 + t) * 32 + (lane & 31);
+                    const float v0 = finish(acc[m][t][i], rl, cs[t], bias[t]), v1 = finish(acc[m][t][i + 1], rl + 1, cs[t], bias[t]);
                     const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(
                                           0, __builtin_bit_cast(int, odd ? v0 : v1), 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
                     const float lo = odd ? got : v0, hi = odd ? v1 : got;
-                    const int rs = rl + (odd ? 1 : 0);
                     if (rs < rows) {
-                        OT *dst = out + (size_t)(p.out_dst ? s_dst[rs] : row0 + rs) * N + (n & ~1);
+                        OT *dst = dst_row + (n & ~1);
                         if constexpr (std::is_same<OT, float>::value)
                             *reinterpret_cast<float2 *>(dst) = make_float2(lo, hi);
                         else if constexpr (std::is_same<OT, _Float16>::value)
