@@ -362,7 +362,9 @@ def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g):
                                                    (40, 2, 5, 1024, 256, 4, 7),        # few experts: several row groups per expert, pruned rows
                                                    (256, 1, 8, 512, 2048, 8, 0),       # most assignments one launch takes
                                                    (37, 1, 9, 1024, 128, 8, 11),       # 8-bit slabs of 32 blocks, empty experts likely
-                                                   (3, 2, 64, 2048, 128, 4, 1)])       # 4-bit slabs of 32 blocks, nearly every expert empty
+                                                   (3, 2, 64, 2048, 128, 4, 1),        # 4-bit slabs of 32 blocks, nearly every expert empty
+                                                   (64, 1, 1, 1024, 256, 4, 5),        # one expert takes every row: four row groups
+                                                   (128, 2, 8, 512, 2048, 8, 0)])      # 256 assignments with two experts per token
 def test_gated_ffn_matches_oracle(T, k, E, d, F, bits, prune):
     """Permutation rebuilt inside fc1: index arrays bit-exact with the oracle's stable sort, y_perm within tolerance."""
     _say(f"gated ffn T={T} k={k} E={E} d={d} F={F} bits={bits} pruned={prune}")
