@@ -49,6 +49,10 @@ struct GemmArgs {
 constexpr int kGatedMaxAssign = 256;    // assignments the fused permutation takes: one per thread of a block
 
 int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);
+void launch_tiled_4_f16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_4_bf16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_8_f16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_8_bf16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
 int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hipStream_t s);
 bool stream_gemm_supports(int K, int bits, int smode);
 int stream_gemm_fit_rows(int K);
