@@ -4,8 +4,9 @@
 // Tokens are the MFMA A operand (rows), weights the B operand (columns).  A wavefront fetches
 // its weight fragments straight from HBM into registers (one 16-byte load per lane per 1 KB
 // fragment block, see moe_common.h), converts the codes to FP16 with the 0x6400 trick and
-// feeds v_mfma_f32_32x32x16_f16; only the activations go through LDS, shared by the four
-// wavefronts of a block, each of which owns its own 64 output channels.
+// feeds v_mfma_f32_32x32x16_f16; only the activations go through LDS (FP16 rows straight from
+// global memory, bf16 rows converted on the way), shared by the four wavefronts of a block, each
+// of which owns its own 64 output channels.
 #pragma once
 #include <type_traits>
 
