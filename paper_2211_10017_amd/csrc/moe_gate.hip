@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
 
     // wave-private staging areas: x [ntok][128] and (NE == 1) the gate weight block [128][E]
     constexpr bool WLDS = NE == 1;
-    const size_t x_halfs = (GM == 1 && NE == 1) ? 0 : (size_t)ntok * kGateBlk;   // (x through scalar loads: no staging)
+    const size_t x_halfs = (GM == 1 && NE == 1 && !BF16) ? 0 : (size_t)ntok * kGateBlk;   // (x through scalar loads: no staging)
     const size_t wave_halfs = x_halfs + (WLDS ? (size_t)kGateWRow * kGateBlk : 0);
     uint16_t *xs = reinterpret_cast<uint16_t *>(smem) + (size_t)wave * wave_halfs;
     uint16_t *ws = xs + x_halfs;
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     // GM == 1 and at most 64 experts (a lane group is the whole wavefront): a token's features are
     // the same for every lane, so they are fetched with scalar loads and feed the MACs from scalar
     // registers; no x staging.  (With more experts per lane the scalar registers run out.)
-    constexpr bool SX = GM == 1 && NE == 1;
+    constexpr bool SX = GM == 1 && NE == 1 && !BF16;   // (bf16 features would be widened in scalar registers, two per dword: they run out)
     constexpr int XR = SX ? 1 : (GM * TB >= 4 ? GM * TB / 4 : 1);   // x vectors per lane per turn (ntok <= GM * TB rows, 4 rows per pass)
     constexpr int WR = WLDS ? 16 : 1;             // gate-weight vectors per lane per turn (128 x E halfs, E <= 64)
     struct Staged { u32x4 x[XR]; u32x4 w[WR]; };
@@ -338,7 +338,8 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     // most of the chip idle
     const int tb = (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
-    const size_t wave_halfs = (tb == 16 && NE == 1 ? 0 : (size_t)ntok * kGateBlk) + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
+    const bool bf = act_dtype == MOE_BF16;
+    const size_t wave_halfs = (tb == 16 && NE == 1 && !bf ? 0 : (size_t)ntok * kGateBlk) + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
     const size_t part_bytes = (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;      // shares the staging space
     const size_t smem = (size_t)4 * wave_halfs * 2 > part_bytes ? (size_t)4 * wave_halfs * 2 : part_bytes;
     dim3 grid((T + ntok - 1) / ntok), block(256);
@@ -361,7 +362,6 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
         else if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4, 8);                                              \
         else MOE_GATE_LAUNCH(BF, NEV, 1, 8);                                                           \
     } while (0)
-    const bool bf = act_dtype == MOE_BF16;
     if (NE == 1) { if (bf) MOE_GATE_TB(true, 1); else MOE_GATE_TB(false, 1); }
     else if (NE == 2) { if (bf) MOE_GATE_TB(true, 2); else MOE_GATE_TB(false, 2); }
     else { if (bf) MOE_GATE_TB(true, 4); else MOE_GATE_TB(false, 4); }

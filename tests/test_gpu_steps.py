@@ -48,7 +48,7 @@ def test_quantize_bit_exact(bits, g, E, K, N):
 @pytest.mark.parametrize("T,d,E,k,act", [
     (64, 1024, 32, 2, "f16"), (37, 64, 1, 1, "f16"), (130, 192, 3, 2, "f16"), (256, 512, 8, 1, "f16"),
     (100, 640, 64, 2, "bf16"), (77, 2048, 128, 2, "f16"), (33, 256, 100, 1, "bf16"), (19, 128, 200, 2, "f16"),
-    (5, 4096, 64, 2, "f16"), (4133, 256, 64, 2, "f16"), (4100, 128, 130, 1, "bf16")])
+    (5, 4096, 64, 2, "f16"), (4133, 256, 64, 2, "f16"), (4100, 128, 130, 1, "bf16"), (4133, 264, 64, 2, "bf16")])
 def test_gate_routing_bit_exact(T, d, E, k, act):
     _say(f"gate T={T} d={d} E={E} k={k} {act}")
     rng = np.random.default_rng(T + d + E)
