@@ -198,6 +198,20 @@ __device__ inline void wait_loads()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
 }
 
+// Inclusive prefix sum over the 64 lanes in the VALU's data-parallel primitives: shifts by 1, 2, 4
+// and 8 inside each row of 16 lanes (zero shifted in), then the last lane of rows 0 and 2 added to rows
+// 1 and 3, then lane 31 added to rows 2 and 3.  All lanes must be active.
+__device__ inline int wave_inclusive_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);     // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);     // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);     // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);     // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);    // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);    // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // Work distribution of the tiled kernel.  A work item is (expert, column block, row tile); the
 // items are ordered expert-major, then by column block, row tile fastest, so that neighbours in
 // the order share a weight column block (row tiles of one expert) or an activation row tile
@@ -221,15 +235,22 @@ __device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, i
                                  int *e_out, int *col, int *row0, int *rows)
 {
     const int lane = threadIdx.x & 63;
-    int total = 0;                                     // row tiles of all experts
-    for (int e0 = 0; e0 < E; e0 += 64) {
+    // row tiles of the experts of one 64-lane chunk, with their inclusive prefix sum over the chunk
+    auto chunk_tiles = [&](int e0, int &lo, int &hi, int &tiles, int &incl) {
         const int e = e0 + lane;
-        int lo = 0, hi = 0;
+        lo = 0, hi = 0;
         if (e < E) expert_range(offsets, e, R, &lo, &hi);
-        const int m = hi - lo;
-        int tiles = m > row_lo ? (m + BM - 1) / BM : 0;
-        for (int off = 32; off > 0; off >>= 1) tiles += __shfl_xor(tiles, off);
-        total += tiles;
+        tiles = hi - lo > row_lo ? (hi - lo + BM - 1) / BM : 0;
+        incl = wave_inclusive_sum(tiles);
+    };
+    int total = 0;                                     // row tiles of all experts
+    int lo0, hi0, tiles0, incl0;                       // the first chunk is kept: with E <= 64 the offsets are read once
+    chunk_tiles(0, lo0, hi0, tiles0, incl0);
+    total = __shfl(incl0, 63);
+    for (int e0 = 64; e0 < E; e0 += 64) {
+        int lo, hi, tiles, incl;
+        chunk_tiles(e0, lo, hi, tiles, incl);
+        total += __shfl(incl, 63);
     }
     const long items = (long)total * ncol;
     const long chunk = (items + kXcds - 1) / kXcds;
@@ -238,15 +259,8 @@ __device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, i
     if (s >= chunk || item >= items) return false;
     int base = 0;
     for (int e0 = 0; e0 < E; e0 += 64) {
-        const int e = e0 + lane;
-        int lo = 0, hi = 0;
-        if (e < E) expert_range(offsets, e, R, &lo, &hi);
-        const int tiles = hi - lo > row_lo ? (hi - lo + BM - 1) / BM : 0;
-        int incl = tiles;
-        for (int off = 1; off < 64; off <<= 1) {
-            const int up = __shfl_up(incl, off);
-            if (lane >= off) incl += up;
-        }
+        int lo = lo0, hi = hi0, tiles = tiles0, incl = incl0;
+        if (e0) chunk_tiles(e0, lo, hi, tiles, incl);
         const uint64_t hit = __ballot((long)(base + incl) * ncol > item);
         if (hit) {
             const int src = __ffsll((unsigned long long)hit) - 1;
