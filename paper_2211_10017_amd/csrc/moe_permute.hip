@@ -78,10 +78,12 @@ __global__ __launch_bounds__(256) void permute_index_kernel(const int32_t *__res
             for (int w = 0; w < 4; ++w) c[w] = sm[w * NB + e];
             total = c[0] + c[1] + c[2] + c[3];
         } else {
-            for (int j = 0; j < nwc; ++j) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) c[w] = hist[(size_t)(blk * 4 + w) * NB + e];
+#pragma unroll 16
+            for (int j = 0; j < nwc; ++j) {              // independent loads: many in flight
                 const int v = hist[(size_t)j * NB + e];
-                if (j < blk * 4) before += v;
-                if (j >= blk * 4 && j < blk * 4 + 4) c[j - blk * 4] = v;
+                before += j < blk * 4 ? v : 0;
                 total += v;
             }
         }
