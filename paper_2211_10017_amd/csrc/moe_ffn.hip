@@ -72,7 +72,6 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     using namespace moe;
     const bool stream_ok = !bf && stream_gemm_supports(g.K, bits, smode);
     const int mean = (g.R + g.E - 1) / g.E;
-    const int fit = stream_gemm_fit_rows(g.K);          // rows of an expert the streaming kernel holds in LDS
     // Few rows per expert on average and a bound that needs at most 16 row groups: every expert
     // streams its weights once per group of `fit` rows (the groups of one expert run together and
     // share the stream in L2), which beats row tiles whose K loops would run on a handful of blocks.
@@ -85,13 +84,9 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
         return launch_stream_gemm(g, bits, smode, max_rows, s);
     }
     if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: these sizes do not run in the straight-line kernel");
-    if (stream_ok && mean <= 96) {
-        g.row_hi = fit;
-        int rc = launch_stream_gemm(g, bits, smode, max_rows, s);
-        if (rc) return rc;
-        g.row_lo = fit;
-        return launch_tiled_gemm(g, bits, smode, bf, s);
-    }
+    // Everything else runs in the tiled kernel, experts with a handful of rows included: their tiles skip
+    // the row blocks that hold no rows and stream the weights as fast as the streaming kernel would
+    // (sending them there in a launch of their own measured 2-25 % slower on skewed loads).
     g.row_lo = 0;
     return launch_tiled_gemm(g, bits, smode, bf, s);
 }
@@ -105,7 +100,9 @@ static bool tiled_only(int R, int E, int max_rows, int d, int F, int bits, bool 
     const int smode = grouped ? SCALE_GROUP : SCALE_CHANNEL;
     for (int K : {d, F}) {
         const bool stream_ok = !bf && stream_gemm_supports(K, bits, smode);
-        if (stream_ok && (max_rows <= 64 || mean <= 96)) return false;
+        const bool few = stream_ok && stream_unrolled_supports(K, bits, smode) && mean <= 32 &&
+                         max_rows <= 16 * stream_unrolled_fit(K, max_rows);
+        if (stream_ok && (max_rows <= 64 || few)) return false;
     }
     return true;
 }
