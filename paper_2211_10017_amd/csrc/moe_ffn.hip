@@ -2,7 +2,7 @@
 // (Sec. 3.3 grouped GEMM, Sec. 3.4 fused dequantisation).  This file holds the entry point:
 // argument checks, workspace layout and the choice between the weight-streaming kernel
 // (experts with few rows, HBM-bound) and the LDS-tiled kernel (experts with many rows,
-// MFMA-bound); both may run in one call when the routed loads are mixed.
+// MFMA-bound).
 #include "moe_ffn_common.h"
 
 namespace moe {
@@ -77,8 +77,7 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     // share the stream in L2), which beats row tiles whose K loops would run on a handful of blocks.
     const bool unrolled = stream_ok && stream_unrolled_supports(g.K, bits, smode);
     const bool few = unrolled && mean <= 32 && max_rows <= 16 * stream_unrolled_fit(g.K, max_rows);
-    if (stream_ok && (max_rows <= 64 || few)) {
-        g.row_hi = 0x7fffffff;                 // every expert streams, `fit` rows per block
+    if (stream_ok && (max_rows <= 64 || few)) {         // every expert streams, `fit` rows per block
         if (unrolled) return launch_stream_unrolled(g, bits, max_rows, s);
         if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel", g.K);
         return launch_stream_gemm(g, bits, smode, max_rows, s);
@@ -87,7 +86,6 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     // Everything else runs in the tiled kernel, experts with a handful of rows included: their tiles skip
     // the row blocks that hold no rows and stream the weights as fast as the streaming kernel would
     // (sending them there in a launch of their own measured 2-25 % slower on skewed loads).
-    g.row_lo = 0;
     return launch_tiled_gemm(g, bits, smode, bf, s);
 }
 
@@ -310,7 +308,7 @@ extern "C" int moe_grouped_gemm_wq(const void *x_perm, const int32_t *expert_off
     GemmArgs g{};
     g.a = (const uint16_t *)x_perm; g.offsets = expert_offsets; g.wq = (const uint8_t *)w_packed;
     g.scales = (const __half *)scales; g.bias = nullptr; g.out = y; g.E = E; g.R = R; g.K = K; g.N = N; g.g = K;
-    g.out_dtype = y_dtype; g.act = MOE_ACT_NONE; g.row_lo = 0; g.row_hi = 0x7fffffff;
+    g.out_dtype = y_dtype; g.act = MOE_ACT_NONE;
     hipStream_t s = as_stream(stream);
     if (bits == 16 || native_convert) return launch_stream_unrolled_variant(g, bits, native_convert != 0, max_rows, s);
     return launch_stream_unrolled(g, bits, max_rows, s);

@@ -23,9 +23,7 @@ struct GemmArgs {
     int E, R, K, N, g;
     int out_dtype;
     int act;                  // MOE_ACT_NONE (plain GEMM) | MOE_ACT_RELU | MOE_ACT_GELU applied after the bias
-    int row_lo;               // tiled kernel: only experts with more than row_lo rows
     int tile_units;           // tiled kernel: row tiles of at most 32 * tile_units rows (set by the launcher)
-    int row_hi;               // streaming kernel: only experts with 1..row_hi rows
     // tiled kernel only: rows fetched / stored through the routing index instead of a permuted copy
     const int32_t *a_src;     // [R] or null: row r of A is a[a_src[r] / a_div]
     int a_div;
@@ -231,7 +229,7 @@ __device__ inline void expert_range(const int32_t *offsets, int e, int R, int *l
     *hi = min(max(offsets[e + 1], l), R);
 }
 
-__device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, int row_lo, int ncol, int wg,
+__device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, int ncol, int wg,
                                  int *e_out, int *col, int *row0, int *rows)
 {
     const int lane = threadIdx.x & 63;
@@ -240,7 +238,7 @@ __device__ inline bool find_item(const int32_t *offsets, int E, int R, int BM, i
         const int e = e0 + lane;
         lo = 0, hi = 0;
         if (e < E) expert_range(offsets, e, R, &lo, &hi);
-        tiles = hi - lo > row_lo ? (hi - lo + BM - 1) / BM : 0;
+        tiles = (hi - lo + BM - 1) / BM;
         incl = wave_inclusive_sum(tiles);
     };
     int total = 0;                                     // row tiles of all experts

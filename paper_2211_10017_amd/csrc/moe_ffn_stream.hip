@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
     int e_lo, e_hi;
     expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
     const int m = e_hi - e_lo;
-    if (m <= 0 || m > p.row_hi || (int)blockIdx.z * fit >= m) return;   // same for the whole block
+    if (m <= 0 || (int)blockIdx.z * fit >= m) return;   // same for the whole block
     const int lo = e_lo + blockIdx.z * fit;
     const int rows = min(fit, m - (int)blockIdx.z * fit);
     const int KB = K / FK;                              // fragment blocks per slab, a multiple of kRing
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256, 2) void stream_unrolled_kernel(GemmArgs p, int
         expert_range(p.offsets, e, p.R, &e_lo, &e_hi);
     }
     const int m = e_hi - e_lo;
-    if (m <= 0 || m > p.row_hi || z * fit >= m) return;   // same for the whole block
+    if (m <= 0 || z * fit >= m) return;   // same for the whole block
     const int lo = e_lo + z * fit;
     const int rows = min(fit, m - z * fit);
     const int ntiles = N / 32;
@@ -517,14 +517,13 @@ bool stream_unrolled_takes_gate(int K, int bits)
 int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int max_rows, hipStream_t s)
 {
     const int kb = p.K / (bits == 4 ? 64 : bits == 8 ? 32 : 16);
-    const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
-    const int fit = unrolled_fit_rows(p.K, most);
+    const int fit = unrolled_fit_rows(p.K, max_rows);
     if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: E=%d exceeds one launch", p.E);
-    if (bits == 16 && kb == 64 && !native) launch_unrolled<16, 64, 1, 4>(p, fit, most, s);
-    else if (bits == 16 && kb == 32 && !native) launch_unrolled<16, 32, 1, 1>(p, fit, most, s);
-    else if (bits == 16 && kb == 16 && !native) launch_unrolled<16, 16, 1, 1>(p, fit, most, s);
-    else if (bits == 4 && kb == 16 && native) launch_unrolled<4, 16, 1, 1, true>(p, fit, most, s);
-    else if (bits == 8 && kb == 32 && native) launch_unrolled<8, 32, 1, 1, true>(p, fit, most, s);
+    if (bits == 16 && kb == 64 && !native) launch_unrolled<16, 64, 1, 4>(p, fit, max_rows, s);
+    else if (bits == 16 && kb == 32 && !native) launch_unrolled<16, 32, 1, 1>(p, fit, max_rows, s);
+    else if (bits == 16 && kb == 16 && !native) launch_unrolled<16, 16, 1, 1>(p, fit, max_rows, s);
+    else if (bits == 4 && kb == 16 && native) launch_unrolled<4, 16, 1, 1, true>(p, fit, max_rows, s);
+    else if (bits == 8 && kb == 32 && native) launch_unrolled<8, 32, 1, 1, true>(p, fit, max_rows, s);
     else return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_gemm_wq: no kernel for bits=%d K=%d convert=%d", bits, p.K, (int)native);
     return check_launch("moe_grouped_gemm_wq");
 }
@@ -532,8 +531,7 @@ int launch_stream_unrolled_variant(const GemmArgs &p, int bits, bool native, int
 int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_t s)
 {
     const int kb = p.K / (bits == 4 ? 64 : 32);
-    const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
-    const int fit = unrolled_fit_rows(p.K, most);
+    const int fit = unrolled_fit_rows(p.K, max_rows);
     if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: E=%d exceeds one launch", p.E);
     // 16 blocks: one slab per wavefront; 64 blocks: K split over the block's wavefronts, two slabs per
     // block (LDS holds two such blocks per CU: with one slab each the launch would need two rounds
@@ -542,22 +540,22 @@ int launch_stream_unrolled(const GemmArgs &p, int bits, int max_rows, hipStream_
     if (p.gate_idx) {                           // permutation rebuilt inside the launch
         if (p.n_assign > kGatedMaxAssign || !stream_unrolled_takes_gate(p.K, bits))
             return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: no kernel for K=%d bits=%d with %d assignments", p.K, bits, p.n_assign);
-        if (bits == 4 && kb == 16) launch_unrolled<4, 16, 1, 1, false, true>(p, fit, most, s);
-        else if (bits == 4) launch_unrolled<4, 32, 1, 1, false, true>(p, fit, most, s);
-        else if (kb == 16) launch_unrolled<8, 16, 1, 1, false, true>(p, fit, most, s);
-        else launch_unrolled<8, 32, 1, 1, false, true>(p, fit, most, s);
+        if (bits == 4 && kb == 16) launch_unrolled<4, 16, 1, 1, false, true>(p, fit, max_rows, s);
+        else if (bits == 4) launch_unrolled<4, 32, 1, 1, false, true>(p, fit, max_rows, s);
+        else if (kb == 16) launch_unrolled<8, 16, 1, 1, false, true>(p, fit, max_rows, s);
+        else launch_unrolled<8, 32, 1, 1, false, true>(p, fit, max_rows, s);
         return check_launch("moe_grouped_ffn_wq_gated (straight-line streaming gemm)");
     }
     if (bits == 4) {
-        if (kb == 16) launch_unrolled<4, 16, 1, 1>(p, fit, most, s);
-        else if (kb == 32) launch_unrolled<4, 32, 1, 1>(p, fit, most, s);
-        else if (kb == 48) launch_unrolled<4, 48, 1, 1>(p, fit, most, s);
-        else launch_unrolled<4, 64, 2, 4>(p, fit, most, s);
+        if (kb == 16) launch_unrolled<4, 16, 1, 1>(p, fit, max_rows, s);
+        else if (kb == 32) launch_unrolled<4, 32, 1, 1>(p, fit, max_rows, s);
+        else if (kb == 48) launch_unrolled<4, 48, 1, 1>(p, fit, max_rows, s);
+        else launch_unrolled<4, 64, 2, 4>(p, fit, max_rows, s);
     } else {
-        if (kb == 16) launch_unrolled<8, 16, 1, 1>(p, fit, most, s);
-        else if (kb == 32) launch_unrolled<8, 32, 1, 1>(p, fit, most, s);
-        else if (kb == 48) launch_unrolled<8, 48, 1, 1>(p, fit, most, s);
-        else launch_unrolled<8, 64, 2, 4>(p, fit, most, s);
+        if (kb == 16) launch_unrolled<8, 16, 1, 1>(p, fit, max_rows, s);
+        else if (kb == 32) launch_unrolled<8, 32, 1, 1>(p, fit, max_rows, s);
+        else if (kb == 48) launch_unrolled<8, 48, 1, 1>(p, fit, max_rows, s);
+        else launch_unrolled<8, 64, 2, 4>(p, fit, max_rows, s);
     }
     return check_launch("moe_grouped_ffn_wq (straight-line streaming gemm)");
 }
@@ -582,10 +580,9 @@ int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hip
     if (tpw < 1) tpw = 1;
     if (tpw > kStreamMaxTpw) tpw = kStreamMaxTpw;
     if (p.E > 65535) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: E=%d exceeds one launch", p.E);
-    // row groups: experts handled here have at most min(row_hi, max_rows) rows
+    // row groups: no expert has more than max_rows rows
     const int fit = stream_fit_rows(p.K);
-    const int most = p.row_hi < max_rows ? p.row_hi : max_rows;
-    dim3 grid((ntiles + 4 * tpw - 1) / (4 * tpw), p.E, (most + fit - 1) / fit);
+    dim3 grid((ntiles + 4 * tpw - 1) / (4 * tpw), p.E, (max_rows + fit - 1) / fit);
     if (bits == 4) launch_stream<4>(p, tpw, grid, s);
     else launch_stream<8>(p, tpw, grid, s);
     return check_launch("moe_grouped_ffn_wq (streaming gemm)");

@@ -10,7 +10,7 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
     const int mean = (p.R + p.E - 1) / p.E;
     int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
     if (smode == SCALE_GROUP_ACC && tm > 2) tm = 2;
-    const long most = (long)p.R / (p.row_lo + 1);               // experts that can exceed row_lo rows
+    const long most = p.R;                                      // experts that can hold rows
     const long ncol = (p.N + 255) / 256;
     // Tiles may be lower than the kernel's 32 * tm rows (it skips row tiles that hold no rows): with few
     // column blocks the launch is a handful of rounds of 512 blocks (two per CU), and 96-row tiles

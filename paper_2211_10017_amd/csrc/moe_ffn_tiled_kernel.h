@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: tile addresses stay scalar
     const int K = p.K, N = p.N;
     int e, col, row0, rows;
-    if (!find_item(p.offsets, p.E, p.R, 32 * p.tile_units, p.row_lo, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
+    if (!find_item(p.offsets, p.E, p.R, 32 * p.tile_units, (N + 255) / 256, blockIdx.x, &e, &col, &row0, &rows)) return;
     e = __builtin_amdgcn_readfirstlane(e), col = __builtin_amdgcn_readfirstlane(col);      // the same in every lane: kept in scalar registers
     row0 = __builtin_amdgcn_readfirstlane(row0), rows = __builtin_amdgcn_readfirstlane(rows);
 
