@@ -6,6 +6,8 @@
 // a block take the four partial sums of the contract (128-element blocks of the feature axis
 // dealt round-robin), so the floating-point order is fixed by the definition, not by the
 // launch shape.  Softmax and top-k are butterfly reductions over the EL lanes of a group.
+// FP16 batches of 16384 tokens and more with 64 experts take another mapping, a token per lane
+// (gate_token_lanes_kernel below), with the same order of the additions.
 #include <math.h>
 
 #include <type_traits>
@@ -314,6 +316,141 @@ __global__ __launch_bounds__(256) void gate_kernel(const uint16_t *__restrict__ 
     }   // token slots of this wavefront
 }
 
+// Many tokens, 64 experts: a lane owns one token.  The block's wavefronts are the four partial sums of
+// the contract times 64 / EW slices of the experts; a feature's EW gate weights are the same for every
+// lane, so they come through scalar loads and feed the MACs from scalar registers (one row of the gate
+// weight is 128 contiguous bytes), while each lane walks its own token's features, 32 at a time, one
+// chunk ahead.  Nothing is staged or exchanged until the partial sums meet in LDS; then every wavefront
+// finishes the logits of 64 / NW experts for all 64 tokens and the candidates are merged per token.
+// Same floating-point order of the logits as gate_kernel.  FP16 only (bf16 weights would be widened in
+// scalar registers, which run out).
+template <int EW>
+__global__ __launch_bounds__(256 * (64 / EW)) void gate_token_lanes_kernel(const uint16_t *__restrict__ x,
+                                                               const uint16_t *__restrict__ wg,
+                                                               const float *__restrict__ bias,
+                                                               const uint8_t *__restrict__ finished, int T, int d,
+                                                               int k, int renorm, int32_t *__restrict__ expert_idx,
+                                                               float *__restrict__ expert_scale)
+{
+    constexpr int E = 64, NW = 4 * (E / EW), EPW = E / NW;      // wavefronts per block, experts a wavefront finishes
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *part = reinterpret_cast<float *>(smem);           // [4 partial sums][64 experts][64 tokens]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int p = wave & 3, slice = wave >> 2;
+    const int t = blockIdx.x * 64 + lane;
+    const uint4 *xrow = reinterpret_cast<const uint4 *>(x + (size_t)min(t, T - 1) * d);
+    float acc[EW];
+#pragma unroll
+    for (int e = 0; e < EW; ++e) acc[e] = 0.0f;
+
+    const int nblk = d / kGateBlk;                            // d is a multiple of the block here
+    const int nch = ((nblk - p + 3) / 4) * 4;                 // 32-feature chunks of this partial sum
+    auto first_feature = [&](int c) { return (p + 4 * (c >> 2)) * kGateBlk + (c & 3) * 32; };
+    uint4 nxt[4];
+    if (nch > 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) nxt[v] = xrow[first_feature(0) / 8 + v];
+    }
+#pragma unroll 1
+    for (int c = 0; c < nch; ++c) {
+        uint4 cur[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cur[v] = nxt[v];
+        const int cn = min(c + 1, nch - 1);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) nxt[v] = xrow[first_feature(cn) / 8 + v];
+        const uint32_t *wrow = reinterpret_cast<const uint32_t *>(wg + (size_t)first_feature(c) * E + slice * EW);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const uint32_t xw[4] = {cur[v].x, cur[v].y, cur[v].z, cur[v].w};
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint16_t xb = (uint16_t)(xw[u >> 1] >> (16 * (u & 1)));
+                const uint32_t *w = wrow + (v * 8 + u) * (E / 2);     // uniform address: scalar loads
+#pragma unroll
+                for (int q = 0; q < EW / 2; ++q) {
+                    const uint32_t w2 = w[q];
+                    acc[2 * q] = mac<false>(xb, (uint16_t)w2, acc[2 * q]);
+                    acc[2 * q + 1] = mac<false>(xb, (uint16_t)(w2 >> 16), acc[2 * q + 1]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EW; ++e) part[(p * E + slice * EW + e) * 64 + lane] = acc[e];
+    __syncthreads();
+
+    // wavefront w: logits of experts w * EPW ... for the lane's token, best two of them with ties to
+    // the lower index (experts in ascending order, a later one must be strictly larger)
+    float lg[EPW];
+    float bv = 0.0f, sv = 0.0f;
+    int be = 0, se = 0;
+#pragma unroll
+    for (int j = 0; j < EPW; ++j) {
+        const int e = wave * EPW + j;
+        float l = ((part[e * 64 + lane] + part[(E + e) * 64 + lane]) + part[(2 * E + e) * 64 + lane]) + part[(3 * E + e) * 64 + lane];
+        if (bias) l = l + bias[e];
+        lg[j] = l;
+        const bool first = j == 0 || l > bv;
+        const bool second = !first && (j == 1 || l > sv);
+        sv = first ? bv : second ? l : sv;
+        se = first ? be : second ? e : se;
+        bv = first ? l : bv;
+        be = first ? e : be;
+    }
+    __syncthreads();                                         // the partial sums are used up: candidates take their place
+    float *cand_v = part;                                    // [NW][2][64]
+    int *cand_e = reinterpret_cast<int *>(part + NW * 2 * 64);      // [NW][2][64]
+    float *den_part = part + 2 * NW * 2 * 64;                // [NW][64]
+    cand_v[(wave * 2 + 0) * 64 + lane] = bv;
+    cand_v[(wave * 2 + 1) * 64 + lane] = sv;
+    cand_e[(wave * 2 + 0) * 64 + lane] = be;
+    cand_e[(wave * 2 + 1) * 64 + lane] = se;
+    __syncthreads();
+    // every wavefront merges the candidates of its token, in ascending order of the experts
+    bv = cand_v[lane]; sv = cand_v[64 + lane];
+    be = cand_e[lane]; se = cand_e[64 + lane];
+#pragma unroll
+    for (int c = 2; c < 2 * NW; ++c) {
+        const float l = cand_v[c * 64 + lane];
+        const int e = cand_e[c * 64 + lane];
+        const bool first = l > bv;
+        const bool second = !first && l > sv;
+        sv = first ? bv : second ? l : sv;
+        se = first ? be : second ? e : se;
+        bv = first ? l : bv;
+        be = first ? e : be;
+    }
+    float den = 0.0f;
+#pragma unroll
+    for (int j = 0; j < EPW; ++j) den += expf(lg[j] - bv);
+    den_part[wave * 64 + lane] = den;
+    __syncthreads();
+    if (wave != 0 || t >= T) return;
+    den = den_part[lane];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) den += den_part[w * 64 + lane];
+    if (finished && finished[t]) {
+        // batch pruning (Sec. 3.5): an expert index past the real experts and a zero scale
+        for (int j = 0; j < k; ++j) {
+            expert_idx[k * t + j] = E;
+            expert_scale[k * t + j] = 0.0f;
+        }
+    } else if (k == 1) {
+        expert_idx[t] = be;
+        expert_scale[t] = 1.0f / den;
+    } else {
+        const float e2 = expf(sv - bv);
+        float s0 = 1.0f / den, s1 = e2 / den;
+        if (renorm) { s0 = 1.0f / (1.0f + e2); s1 = e2 / (1.0f + e2); }
+        expert_idx[2 * t] = be;
+        expert_idx[2 * t + 1] = se;
+        expert_scale[2 * t] = s0;
+        expert_scale[2 * t + 1] = s1;
+    }
+}
+
 }  // namespace moe
 
 extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias,
@@ -329,6 +466,15 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     if (E > 256) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: E=%d above 256", E);
     if (act_dtype != MOE_F16 && act_dtype != MOE_BF16) return fail(MOE_ERR_UNSUPPORTED, "moe_gate_topk: act_dtype must be fp16 or bf16");
     if (!aligned16(x) || !aligned16(wg)) return fail(MOE_ERR_INVALID_ARG, "moe_gate_topk: x and wg must be 16-byte aligned");
+    hipStream_t s = as_stream(stream);
+    const bool bf = act_dtype == MOE_BF16;
+    if (!bf && E == 64 && d % kGateBlk == 0 && T >= 16384) {     // a token per lane, and a block of 64 tokens for every CU at least
+        dim3 grid((T + 63) / 64), block(512);
+        const size_t smem = (size_t)4 * 64 * 64 * sizeof(float);
+        hipLaunchKernelGGL((gate_token_lanes_kernel<32>), grid, block, smem, s, (const uint16_t *)x, (const uint16_t *)wg,
+                           bias, finished, T, d, k, renormalize, expert_idx, expert_scale);
+        return check_launch("moe_gate_topk");
+    }
     int EL = 8;
     while (EL < E && EL < 64) EL *= 2;
     const int NE = (E + 63) / 64;
@@ -338,13 +484,11 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     // most of the chip idle
     const int tb = (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
-    const bool bf = act_dtype == MOE_BF16;
     const size_t wave_halfs = (tb == 16 && NE == 1 && !bf ? 0 : (size_t)ntok * kGateBlk) + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
     const size_t part_bytes = (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;      // shares the staging space
     const size_t smem = (size_t)4 * wave_halfs * 2 > part_bytes ? (size_t)4 * wave_halfs * 2 : part_bytes;
     dim3 grid((T + ntok - 1) / ntok), block(256);
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
-    hipStream_t s = as_stream(stream);
 #define MOE_GATE_LAUNCH(BF, NEV, TBV, GMV)                                                             \
     do {                                                                                               \
         static bool raised = false;   /* more than 64 KB of dynamic LDS must be asked for once */       \

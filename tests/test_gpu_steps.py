@@ -48,7 +48,9 @@ def test_quantize_bit_exact(bits, g, E, K, N):
 @pytest.mark.parametrize("T,d,E,k,act", [
     (64, 1024, 32, 2, "f16"), (37, 64, 1, 1, "f16"), (130, 192, 3, 2, "f16"), (256, 512, 8, 1, "f16"),
     (100, 640, 64, 2, "bf16"), (77, 2048, 128, 2, "f16"), (33, 256, 100, 1, "bf16"), (19, 128, 200, 2, "f16"),
-    (5, 4096, 64, 2, "f16"), (4133, 256, 64, 2, "f16"), (4100, 128, 130, 1, "bf16"), (4133, 264, 64, 2, "bf16")])
+    (5, 4096, 64, 2, "f16"), (4133, 256, 64, 2, "f16"), (4100, 128, 130, 1, "bf16"), (4133, 264, 64, 2, "bf16"),
+    # a token per lane (many tokens, 64 experts): ragged last block; one, three and six feature blocks
+    (16400, 256, 64, 2, "f16"), (16384, 128, 64, 1, "f16"), (16501, 384, 64, 2, "f16"), (17000, 768, 64, 1, "f16")])
 def test_gate_routing_bit_exact(T, d, E, k, act):
     _say(f"gate T={T} d={d} E={E} k={k} {act}")
     rng = np.random.default_rng(T + d + E)
@@ -76,6 +78,17 @@ def test_gate_ties_and_equal_logits():
     assert np.array_equal(gi.cpu().numpy(), np.tile([2, 5], (9, 1)))
     gi, gs = B.moe_gate_topk(x[:0], wg, None, 1, True)           # T = 0 is a no-op
     assert gi.shape == (0, 1)
+    # the same with a token per lane (many tokens, 64 experts)
+    x = torch.ones((16389, 128), dtype=torch.float16, device=DEV)
+    wg = torch.zeros((128, 64), dtype=torch.float16, device=DEV)
+    gi, gs = B.moe_gate_topk(x, wg, None, 2, True)
+    assert np.array_equal(gi.cpu().numpy(), np.tile([0, 1], (16389, 1))) and np.allclose(gs.cpu().numpy(), 0.5)
+    wg[0, 7] = 1.0
+    wg[0, 63] = 1.0
+    gi, _ = B.moe_gate_topk(x, wg, None, 2, True)
+    assert np.array_equal(gi.cpu().numpy(), np.tile([7, 63], (16389, 1)))
+    gi, gs = B.moe_gate_topk(x, wg, None, 1, True)
+    assert (gi.cpu().numpy() == 7).all()
 
 
 # ------------------------------------------------------------------ permute
@@ -234,7 +247,7 @@ def test_calls_are_deterministic():
 
 
 # ------------------------------------------------------------------ batch pruning (Sec. 3.5)
-@pytest.mark.parametrize("T,d,E,k", [(64, 1024, 32, 2), (130, 192, 3, 1), (77, 2048, 128, 2)])
+@pytest.mark.parametrize("T,d,E,k", [(64, 1024, 32, 2), (130, 192, 3, 1), (77, 2048, 128, 2), (16400, 128, 64, 2)])
 def test_gate_marks_finished_rows(T, d, E, k):
     _say(f"gate with finished rows T={T} E={E} k={k}")
     rng = np.random.default_rng(T + E)
