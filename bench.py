@@ -159,7 +159,10 @@ def main():
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / MFMA_F16_PEAK_TFLOPS, "traffic": None}
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name) if args.finished == 0 else None
-    roofline.update({"kernel": "stream_unrolled_kernel" if roofline["bound"] == "hbm" else "grouped_gemm_kernel", "launches_per_step": launches_per_ffn,
+    # which GEMM kernel the library's dispatch rule picks for these sizes (bf16 rows and everything the
+    # routing-fused entry point takes run in the LDS-tiled kernel, the rest streams)
+    tiled = w.act == "bf16" or binding.moe_grouped_ffn_wq_routed_supported(w.R, w.E, w.T, w.d, w.F, w.bits, w.group_size, torch.float16)
+    roofline.update({"kernel": "grouped_gemm_kernel" if tiled else "stream_unrolled_kernel", "launches_per_step": launches_per_ffn,
                      "avg_launch_us": launch_s * 1e6, "ffn_us_median": float(np.median(ffn_ms)) * 1e3,
                      "ffn_us_min": float(ffn_ms.min()) * 1e3, "active_experts": active,
                      "algorithmic_bytes_per_step": int(bytes_ffn), "flops_per_step": flops_ffn,
