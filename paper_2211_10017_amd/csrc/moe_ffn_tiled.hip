@@ -8,7 +8,14 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
 {
     // row-tile height from the mean rows per expert (the offsets themselves stay on the device)
     const int mean = (p.R + p.E - 1) / p.E;
-    int tm = mean <= 32 ? 1 : mean <= 64 ? 2 : 4;
+    // 64-row tiles also for taller experts where a third block per CU pays more than halving the
+    // dequantisation does: short K loops (the prologue and epilogue of a block then overlap the loops of
+    // two others, not of one), and 8-bit weights up to 256 rows per expert (their 128-row tile has
+    // registers for one set of weights in flight only)
+#ifndef TM2_SHORT_K
+#define TM2_SHORT_K 2048
+#endif
+    int tm = mean <= 32 ? 1 : (mean <= 64 || p.K <= TM2_SHORT_K || (bits == 8 && mean <= 256)) ? 2 : 4;
     if (smode == SCALE_GROUP_ACC && tm > 2) tm = 2;
     const long most = p.R;                                      // experts that can hold rows
     const long ncol = (p.N + 255) / 256;
