@@ -12,10 +12,7 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
     // dequantisation does: short K loops (the prologue and epilogue of a block then overlap the loops of
     // two others, not of one), and 8-bit weights up to 256 rows per expert (their 128-row tile has
     // registers for one set of weights in flight only)
-#ifndef TM2_SHORT_K
-#define TM2_SHORT_K 2048
-#endif
-    int tm = mean <= 32 ? 1 : (mean <= 64 || p.K <= TM2_SHORT_K || (bits == 8 && mean <= 256)) ? 2 : 4;
+    int tm = mean <= 32 ? 1 : (mean <= 64 || p.K <= 2048 || (bits == 8 && mean <= 256)) ? 2 : 4;
     if (smode == SCALE_GROUP_ACC && tm > 2) tm = 2;
     const long most = p.R;                                      // experts that can hold rows
     const long ncol = (p.N + 255) / 256;
