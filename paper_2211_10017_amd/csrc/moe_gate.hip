@@ -480,9 +480,10 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     const int NE = (E + 63) / 64;
     // tokens per lane group: sixteen when every lane group is a whole wavefront and there are
     // enough tokens to fill the chip that way (each block stages the whole gate weight, so more
-    // tokens per block mean less staging per token); else four; one when even that would leave
-    // most of the chip idle
-    const int tb = (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
+    // tokens per block mean less staging per token), thirty-two for bf16 rows, which go through
+    // LDS (with FP16 rows in scalar registers that many tokens measured twice as slow); else four;
+    // one when even that would leave most of the chip idle
+    const int tb = (bf && EL == 64 && NE == 1 && T / 32 >= 256) ? 32 : (EL == 64 && T / 16 >= 256) ? 16 : ((long)T * EL / 64 + 3) / 4 >= 256 ? 4 : 1;
     const int ntok = (64 / EL) * tb;
     const size_t wave_halfs = (tb == 16 && NE == 1 && !bf ? 0 : (size_t)ntok * kGateBlk) + (NE == 1 ? (size_t)kGateWRow * kGateBlk : 0);
     const size_t part_bytes = (size_t)4 * (NE == 3 ? 4 : NE) * tb * 64 * 4;      // shares the staging space
@@ -506,7 +507,8 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
         else if (tb == 4) MOE_GATE_LAUNCH(BF, NEV, 4, 8);                                              \
         else MOE_GATE_LAUNCH(BF, NEV, 1, 8);                                                           \
     } while (0)
-    if (NE == 1) { if (bf) MOE_GATE_TB(true, 1); else MOE_GATE_TB(false, 1); }
+    if (NE == 1 && tb == 32) MOE_GATE_LAUNCH(true, 1, 32, 1);
+    else if (NE == 1) { if (bf) MOE_GATE_TB(true, 1); else MOE_GATE_TB(false, 1); }
     else if (NE == 2) { if (bf) MOE_GATE_TB(true, 2); else MOE_GATE_TB(false, 2); }
     else { if (bf) MOE_GATE_TB(true, 4); else MOE_GATE_TB(false, 4); }
 #undef MOE_GATE_TB

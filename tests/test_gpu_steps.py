@@ -50,7 +50,9 @@ def test_quantize_bit_exact(bits, g, E, K, N):
     (100, 640, 64, 2, "bf16"), (77, 2048, 128, 2, "f16"), (33, 256, 100, 1, "bf16"), (19, 128, 200, 2, "f16"),
     (5, 4096, 64, 2, "f16"), (4133, 256, 64, 2, "f16"), (4100, 128, 130, 1, "bf16"), (4133, 264, 64, 2, "bf16"),
     # a token per lane (many tokens, 64 experts): ragged last block; one, three and six feature blocks
-    (16400, 256, 64, 2, "f16"), (16384, 128, 64, 1, "f16"), (16501, 384, 64, 2, "f16"), (17000, 768, 64, 1, "f16")])
+    (16400, 256, 64, 2, "f16"), (16384, 128, 64, 1, "f16"), (16501, 384, 64, 2, "f16"), (17000, 768, 64, 1, "f16"),
+    # bf16, 64 experts: thirty-two tokens per lane from 8192 tokens on
+    (8200, 256, 64, 2, "bf16"), (8229, 136, 64, 1, "bf16")])
 def test_gate_routing_bit_exact(T, d, E, k, act):
     _say(f"gate T={T} d={d} E={E} k={k} {act}")
     rng = np.random.default_rng(T + d + E)
