@@ -172,6 +172,12 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
     ([290, 131], 128, 192, 8, 0, "bf16", torch.float32),
     ([270, 257, 1], 192, 256, 4, 0, "f16", torch.float32),          # balanced row tiles: 96+96+78 and 96+96+65
     ([2, 11, 5], 256, 2048, 8, 0, "f16", torch.float16),            # fc2 splits K over the wavefronts, two channel tiles per block
+    # K above 2048 and many rows per expert: the 128-row tiles (shorter K loops and 8-bit weights up to 256 rows run 64-row tiles)
+    ([270, 257, 1], 2112, 2176, 4, 0, "f16", torch.float32),
+    ([300, 270, 259], 2112, 2176, 8, 0, "f16", torch.float16),      # tallest 8-bit tiles: weights fetched one step ahead
+    ([300, 280], 2112, 2176, 8, 64, "f16", torch.float32),
+    ([290, 300], 2112, 2112, 8, 0, "bf16", torch.float32),
+    ([150, 120], 2112, 2112, 4, 64, "bf16", torch.float32),         # two-term group scales in 128-row tiles
 ])
 def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     _say(f"ffn rows={rows} d={d} F={F} bits={bits} g={g} {act} y={y_dt}")
