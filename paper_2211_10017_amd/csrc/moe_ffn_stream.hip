@@ -170,12 +170,10 @@ template <int BITS>
 static void launch_stream(const GemmArgs &p, int tpw, dim3 grid, hipStream_t s)
 {
     // more than 64 KB of dynamic LDS has to be asked for once per kernel
-    static bool raised = false;
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_gemm_kernel<BITS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLds);
-        raised = true;
-    }
+    // (a function-local static is initialised once, also when several threads call)
+    static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_gemm_kernel<BITS>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLds);
+    (void)raised;                               // a refusal shows up as the launch's error
     hipLaunchKernelGGL((stream_gemm_kernel<BITS>), grid, dim3(256), kStreamLds, s, p, tpw);
 }
 
@@ -475,12 +473,9 @@ static void launch_unrolled(const GemmArgs &p, int fit, int max_rows, hipStream_
     int lds = fit * (K + kRowPad) * 2;
     if (KS == 4 && lds < TPW * 4 * 16 * 64 * 4) lds = TPW * 4 * 16 * 64 * 4;
     lds += 256 * 16;
-    static bool raised = false;
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE, PERM>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
-        raised = true;
-    }
+    static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(&stream_unrolled_kernel<BITS, KB, TPW, KS, NATIVE, PERM>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+    (void)raised;
     const int ntiles = p.N / 32;
     const int per_block = KS == 1 ? 4 * TPW : TPW;
     dim3 grid((ntiles + per_block - 1) / per_block, p.E, (max_rows + fit - 1) / fit);

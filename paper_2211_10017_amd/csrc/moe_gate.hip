@@ -492,12 +492,10 @@ extern "C" int moe_gate_topk(const void *x, int act_dtype, const void *wg, const
     const uint16_t *xp = (const uint16_t *)x, *wp = (const uint16_t *)wg;
 #define MOE_GATE_LAUNCH(BF, NEV, TBV, GMV)                                                             \
     do {                                                                                               \
-        static bool raised = false;   /* more than 64 KB of dynamic LDS must be asked for once */       \
-        if (!raised) {                                                                                 \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV, GMV>), \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);          \
-            raised = true;                                                                             \
-        }                                                                                              \
+        /* more than 64 KB of dynamic LDS must be asked for once (a local static: once, also across threads) */ \
+        static const hipError_t raised = hipFuncSetAttribute(reinterpret_cast<const void *>(&gate_kernel<BF, NEV, TBV, GMV>), \
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024); \
+        (void)raised;                                                                                  \
         hipLaunchKernelGGL((gate_kernel<BF, NEV, TBV, GMV>), grid, block, smem, s, xp, wp, bias, finished, T, d, E,\
                            EL, k, renormalize, expert_idx, expert_scale);                              \
     } while (0)
