@@ -65,44 +65,53 @@ extern "C" size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E,
     return moe::ffn_workspace(R, d, F, act_dtype).total;
 }
 
-// Runs one of the two GEMMs of the FFN, choosing kernels from what the host knows about the
-// routed loads: an upper bound on the rows of any expert and the mean rows per expert.
+// Which kernel one GEMM of the FFN runs in, from what the host knows about the routed loads: an upper
+// bound on the rows of any expert and the mean rows per expert.
+enum GemmKernel { GEMM_TILED, GEMM_STREAM_UNROLLED, GEMM_STREAM_LOOP };
+
+static GemmKernel choose_kernel(int R, int E, int max_rows, int K, int N, int bits, int smode, bool bf)
+{
+    using namespace moe;
+    if (bf || !stream_gemm_supports(K, bits, smode)) return GEMM_TILED;
+    const int mean = (R + E - 1) / E;
+    const bool unrolled = stream_unrolled_supports(K, bits, smode);
+    // rows of an expert one block of the streaming kernel holds; an expert with more rows takes further
+    // blocks (row groups), each of which streams the expert's weights again
+    const int fit = unrolled ? stream_unrolled_fit(K, max_rows) : stream_gemm_fit_rows(K);
+    // Streaming takes a row bound that needs few row groups: at most 64 rows, or at most 32 rows per
+    // expert on average and at most sixteen groups ...
+    const bool few = unrolled && mean <= 32 && max_rows <= 16 * fit;
+    if (!(max_rows <= 64 || few)) return GEMM_TILED;
+    // ... and it pays while the typical expert is one row group (measured on 32 experts of 1024 x 4096:
+    // 34 us up to 8 rows per expert, 47 at 16, 69 at 24, against 49 us in row tiles at any of these), or
+    // the batch is decode-sized, or row tiles would leave most of the chip idle (one tile per expert and
+    // column block: 8 experts of 512 x 2048 stream in 16 us and take 30 us in 64 + 16 tiles).
+    const long tiles = (long)(E < R ? E : R) * ((N + 255) / 256);
+    if (R <= 256 || mean <= fit || tiles < 128) return unrolled ? GEMM_STREAM_UNROLLED : GEMM_STREAM_LOOP;
+    return GEMM_TILED;
+}
+
 static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows, hipStream_t s)
 {
     using namespace moe;
-    const bool stream_ok = !bf && stream_gemm_supports(g.K, bits, smode);
-    const int mean = (g.R + g.E - 1) / g.E;
-    // Few rows per expert on average and a bound that needs at most 16 row groups: every expert
-    // streams its weights once per group of `fit` rows (the groups of one expert run together and
-    // share the stream in L2), which beats row tiles whose K loops would run on a handful of blocks.
-    const bool unrolled = stream_ok && stream_unrolled_supports(g.K, bits, smode);
-    const bool few = unrolled && mean <= 32 && max_rows <= 16 * stream_unrolled_fit(g.K, max_rows);
-    if (stream_ok && (max_rows <= 64 || few)) {         // every expert streams, `fit` rows per block
-        if (unrolled) return launch_stream_unrolled(g, bits, max_rows, s);
-        if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel", g.K);
-        return launch_stream_gemm(g, bits, smode, max_rows, s);
-    }
-    if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: these sizes do not run in the straight-line kernel");
+    const GemmKernel kernel = choose_kernel(g.R, g.E, max_rows, g.K, g.N, bits, smode, bf);
+    if (kernel == GEMM_STREAM_UNROLLED) return launch_stream_unrolled(g, bits, max_rows, s);
+    if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel with these sizes", g.K);
+    if (kernel == GEMM_STREAM_LOOP) return launch_stream_gemm(g, bits, smode, max_rows, s);
     // Everything else runs in the tiled kernel, experts with a handful of rows included: their tiles skip
     // the row blocks that hold no rows and stream the weights as fast as the streaming kernel would
     // (sending them there in a launch of their own measured 2-25 % slower on skewed loads).
     return launch_tiled_gemm(g, bits, smode, bf, s);
 }
 
-// true when a call with these sizes runs both GEMMs in the tiled kernel alone (the only kernel
-// that takes rows through the routing index)
+// true when a call with these sizes runs both GEMMs in the tiled kernel (the only kernel that takes
+// rows through the routing index)
 static bool tiled_only(int R, int E, int max_rows, int d, int F, int bits, bool grouped, bool bf)
 {
     using namespace moe;
-    const int mean = (R + E - 1) / E;
     const int smode = grouped ? SCALE_GROUP : SCALE_CHANNEL;
-    for (int K : {d, F}) {
-        const bool stream_ok = !bf && stream_gemm_supports(K, bits, smode);
-        const bool few = stream_ok && stream_unrolled_supports(K, bits, smode) && mean <= 32 &&
-                         max_rows <= 16 * stream_unrolled_fit(K, max_rows);
-        if (stream_ok && (max_rows <= 64 || few)) return false;
-    }
-    return true;
+    return choose_kernel(R, E, max_rows, d, F, bits, smode, bf) == GEMM_TILED &&
+           choose_kernel(R, E, max_rows, F, d, bits, smode, bf) == GEMM_TILED;
 }
 
 static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
@@ -242,12 +251,12 @@ static int gated_shapes(int T, int k, int E, int d, int F, int bits, int group_s
     if (T <= 0 || k < 1 || k > 2 || E <= 0 || d <= 0 || F <= 0 || act_dtype != MOE_F16) return 0;
     if ((long)T * k > kGatedMaxAssign || (bits != 4 && bits != 8) || d % 64 || F % 64) return 0;
     if (group_size != 0 && !(group_size == d && group_size == F)) return 0;
-    if (!stream_unrolled_supports(d, bits, SCALE_CHANNEL) || !stream_unrolled_takes_gate(d, bits)) return 0;
-    // the dispatch rule of run_gemm must send fc1 to the straight-line kernel alone (row bound T)
-    const int R = T * k, mean = (R + E - 1) / E;
-    if (!(T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(d, T)))) return 0;
+    if (!stream_unrolled_takes_gate(d, bits)) return 0;
+    // fc1 must run in the straight-line streaming kernel (row bound T) ...
+    const int R = T * k;
+    if (choose_kernel(R, E, T, d, F, bits, SCALE_CHANNEL, false) != GEMM_STREAM_UNROLLED) return 0;
     // ... and fc2 as well, if it is to add its rows straight into the layer output
-    const bool fc2 = stream_unrolled_supports(F, bits, SCALE_CHANNEL) && (T <= 64 || (mean <= 32 && T <= 16 * stream_unrolled_fit(F, T)));
+    const bool fc2 = choose_kernel(R, E, T, F, d, bits, SCALE_CHANNEL, false) == GEMM_STREAM_UNROLLED;
     return fc2 ? 2 : 1;
 }
 

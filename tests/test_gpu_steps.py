@@ -123,7 +123,7 @@ def test_permute_no_tokens():
 
 
 # ------------------------------------------------------------------ grouped FFN
-def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, activation="relu"):
+def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, activation="relu", bound=0):
     rng = np.random.default_rng(seed)
     E = len(rows_per_expert)
     off = np.concatenate([[0], np.cumsum(rows_per_expert)]).astype(np.int32)
@@ -143,7 +143,7 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
         ob2 = rng.standard_normal((E, d)).astype(np.float16).astype(np.float32) * 0.1
         b1, b2 = to_dev(ob1, torch.float16), to_dev(ob2, torch.float16)
     y = B.moe_grouped_ffn_wq(x, to_dev(off, torch.int32), E, d, F, bits, g, p1, s1, p2, s2, b1, b2, y_dtype=y_dt,
-                             activation=activation)
+                             activation=activation, max_rows_per_expert=bound)
     torch.cuda.synchronize()
     want = oracle.grouped_ffn(x.float().cpu().numpy(), off, q1, os1, q2, os2, g, oracle_dtype_code(tdt), ob1, ob2,
                               activation=B.ACTIVATIONS[activation])
@@ -182,6 +182,22 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
 def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     _say(f"ffn rows={rows} d={d} F={F} bits={bits} g={g} {act} y={y_dt}")
     got, want = _ffn_case(rows, d, F, bits, g, act, y_dt, seed=sum(rows) + d + bits)
+    max_abs, rel = error_metrics(got, want)
+    _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
+@pytest.mark.parametrize("rows,d,F,bits", [
+    # a row bound of at most 64, but several row groups per expert and enough row tiles to fill the chip: the tiled kernel
+    ([40, 37, 44, 40, 1, 40, 39, 40, 64, 40, 33, 40], 1024, 4096, 4),
+    # fc1 in row tiles, fc2 (two column blocks: too few tiles) in the run-loop streaming kernel
+    ([20] * 14, 512, 2560, 8),
+    # decode-sized: both GEMMs stream whatever the rows per expert
+    ([60, 64, 3], 1024, 4096, 4),
+])
+def test_grouped_ffn_with_a_row_bound_matches_oracle(rows, d, F, bits):
+    _say(f"ffn with row bound rows={rows} d={d} F={F} bits={bits}")
+    got, want = _ffn_case(rows, d, F, bits, 0, "f16", torch.float32, seed=sum(rows) + bits, bound=max(rows))
     max_abs, rel = error_metrics(got, want)
     _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
