@@ -135,9 +135,11 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  *       every range into [0, R], so other contents give wrong results but no stray access.
  *   max_rows_per_expert: an upper bound on the rows any one expert receives, if the caller
  *       knows one (T is one: a token visits an expert at most once); 0 = unknown (R is used).
- *       It chooses between the weight-streaming kernels (bound <= 64, or a mean of at most 32
- *       rows per expert with a bound of at most sixteen row groups) and the tiled kernel, and
- *       sizes the streaming launch, so it must be a true bound: rows of an expert beyond it
+ *       It takes part in the choice between the weight-streaming kernels (which need a bound
+ *       <= 64, or a mean of at most 32 rows per expert with a bound of at most sixteen row
+ *       groups, and are used while R / E says that the typical expert fits one row group, R <= 256,
+ *       or there are too few experts to fill the chip with row tiles) and the tiled kernel, and
+ *       it sizes the streaming launch, so it must be a true bound: rows of an expert beyond it
  *       are not computed.
  *   w1_packed / w2_packed: q_packed from moe_quantize_experts for (E,d,F) / (E,F,d)
  *   s1 fp16 [E, d/g, F]; s2 fp16 [E, F/g, d]  (g = group_size, or K when group_size is 0)
