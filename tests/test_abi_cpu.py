@@ -68,6 +68,10 @@ def test_fused_entry_points_say_on_the_host_what_they_take(lib):
     assert lib.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, F16) == 1
     assert lib.moe_grouped_ffn_wq_routed_supported(16384, 64, 8192, 4096, 16384, 4, 128, BF16) == 0
     assert lib.moe_grouped_ffn_wq_routed_supported(128, 32, 64, 1024, 4096, 4, 0, F16) == 0
+    # a row bound of 64 alone does not mean streaming: 64 rows per expert are several row groups each, so row tiles
+    assert lib.moe_grouped_ffn_wq_routed_supported(8192, 128, 64, 2048, 8192, 8, 0, F16) == 1
+    assert lib.moe_grouped_ffn_wq_routed_supported(512, 128, 64, 2048, 8192, 8, 0, F16) == 0      # 4 rows per expert: one group, streams
+    assert lib.moe_grouped_ffn_wq_routed_supported(256, 8, 256, 512, 2048, 8, 0, F16) == 0        # decode-sized: streams
     # permutation rebuilt inside fc1: decode sizes only; 2 = the un-permute may be fused in as well
     assert lib.moe_grouped_ffn_wq_gated_supported(64, 2, 32, 1024, 4096, 4, 0, F16) == 2        # the decode workload
     assert lib.moe_grouped_ffn_wq_gated_supported(256, 1, 8, 512, 2048, 8, 0, F16) == 2         # 256 assignments: the most
