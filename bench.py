@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the grouped GEMM, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
 # runs of this file (profiles/stream_unrolled_c2_traffic.md, profiles/grouped_gemm_c5_counters.md): counter readings scaled by what the same
 # counters read for a plain 256 MiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 71.3e6, "c5": 4.30e9}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"c2": 71.1e6, "c5": 4.30e9}
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X dense fp16 MFMA
