@@ -42,6 +42,17 @@ __device__ inline void static_for(F &&f)
 
 constexpr int kStreamMaxTpw = 4;       // slabs per wavefront (their scales are fetched up front)
 
+// One 16-byte weight load of the ring.  The weights of a launch are read once and are many times the
+// L2: loaded as non-temporal they leave it first, so the small arrays every block starts from (gate
+// indices, offsets, activation rows) and the gate's inputs of the next step stay cached (decode
+// workload: 45.8 -> 43.6 us per step).
+__device__ inline uint4 ring_load(const uint4 *p)
+{
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int BITS>
 __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw)
 {
@@ -76,7 +87,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
     uint4 Wn[kRing];                                    // the run in flight
     if (nblk) {
 #pragma unroll
-        for (int i = 0; i < kRing; ++i) Wn[i] = wbase[(size_t)i * 64];
+        for (int i = 0; i < kRing; ++i) Wn[i] = ring_load(wbase + (size_t)i * 64);
     }
     // per-channel scale and bias of this wavefront's slabs (fetched now: a compiler-issued load
     // inside the ring loop would be waited for with vmcnt(0) and drain the ring)
@@ -126,7 +137,7 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
             for (int i = 0; i < kRing; ++i) Wc[i] = Wn[i];
             if (sl * KB + kb0 + 2 * kRing <= nblk) {
 #pragma unroll
-                for (int i = 0; i < kRing; ++i) Wn[i] = wnext[(size_t)i * 64];
+                for (int i = 0; i < kRing; ++i) Wn[i] = ring_load(wnext + (size_t)i * 64);
                 wnext += (size_t)kRing * 64;
             }
             fetch_a(0, kb0);
@@ -194,24 +205,6 @@ __device__ inline void add_to_token(const GemmArgs &p, int r, int n, float v)
 {
     const int a = p.out_dst[r];
     unsafeAtomicAdd(reinterpret_cast<float *>(p.out) + (size_t)(a / p.out_div) * p.N + n, v * p.out_scale[a]);
-}
-
-// One 16-byte weight load of the ring.  The weights of a launch are read once and are many times the
-// L2: loaded as non-temporal they leave it first, so the small arrays every block starts from (gate
-// indices, offsets, activation rows) and the gate's inputs of the next step stay cached (decode
-// workload: 45.8 -> 43.6 us per step).
-#ifndef RING_NT
-#define RING_NT 1
-#endif
-__device__ inline uint4 ring_load(const uint4 *p)
-{
-#if RING_NT
-    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-#else
-    return *p;
-#endif
 }
 
 //
