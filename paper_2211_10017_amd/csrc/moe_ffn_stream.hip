@@ -82,13 +82,6 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
     const uint4 *wbase = reinterpret_cast<const uint4 *>(p.wq + (size_t)e * packed_bytes_per_expert(K, N, BITS) +
                                                          (size_t)t0c * KB * kFragBytes) + lane;
 
-    // the first run of weight blocks is requested before anything else, so that it is in flight
-    // while the rows are staged
-    uint4 Wn[kRing];                                    // the run in flight
-    if (nblk) {
-#pragma unroll
-        for (int i = 0; i < kRing; ++i) Wn[i] = ring_load(wbase + (size_t)i * 64);
-    }
     // per-channel scale and bias of this wavefront's slabs (fetched now: a compiler-issued load
     // inside the ring loop would be waited for with vmcnt(0) and drain the ring)
     float cs[kStreamMaxTpw], bias[kStreamMaxTpw];
@@ -106,6 +99,14 @@ __global__ __launch_bounds__(256, 2) void stream_gemm_kernel(GemmArgs p, int tpw
             for (int col = threadIdx.x; col < vpr; col += 256)
                 *reinterpret_cast<uint4 *>(lds_a + r * ldr + col * 8) =
                     *reinterpret_cast<const uint4 *>(a_rows + (size_t)r * K + col * 8);
+    }
+    // The first run of weight blocks is requested once the rows are on their way into LDS, not before:
+    // the load counter is in order, so rows requested behind 16 KB of weights per wavefront would be
+    // waited for until all of those have arrived.
+    uint4 Wn[kRing];                                    // the run in flight
+    if (nblk) {
+#pragma unroll
+        for (int i = 0; i < kRing; ++i) Wn[i] = ring_load(wbase + (size_t)i * 64);
     }
     __syncthreads();
     if (nblk == 0) return;
