@@ -16,10 +16,17 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is
  *     enqueued on it; no entry point synchronises with the host or reads device memory from
  *     the host (the per-expert offsets stay on the device).
- *   - Return value: MOE_OK or one of the MOE_ERR_* codes.  Arguments are validated on the host
- *     before anything is launched; on error nothing has been enqueued, and
+ *   - Return value: MOE_OK or one of the MOE_ERR_* codes.  Arguments, sizes and the choice of
+ *     kernels are checked on the host before anything is launched: with MOE_ERR_INVALID_ARG,
+ *     MOE_ERR_UNSUPPORTED or MOE_ERR_WORKSPACE nothing has been enqueued.  MOE_ERR_HIP reports a
+ *     launch the runtime refused; launches of the same call made before it stay enqueued.
  *     moe_last_error() returns a thread-local message.  No exceptions, no aborts.
- *   - Identical inputs give bit-identical outputs (no floating-point atomics, stable sort).
+ *   - Identical inputs give bit-identical outputs: the sort is stable and no result depends on
+ *     the order in which workgroups run.  (One path adds floating-point numbers into shared
+ *     memory locations, moe_grouped_ffn_wq_gated with expert_scale: at most two fp32 terms per
+ *     element onto a cleared buffer, and the sum of two terms does not depend on their order.)
+ *   - Limits of a whole layer call: 1 <= k <= 2 and k <= E <= 256 (the gate's limits; moe_permute
+ *     alone takes E <= 1024 and the FFN entry points E <= 4096), d % 64 == 0, F % 64 == 0.
  *   - Notation: T tokens, d = d_model, F = d_ff, E experts, k experts per token,
  *     R = T*k routed rows, assignment id a = t*k + j.  Expert weights are (E, K, N)
  *     row-major with N contiguous, so that a GEMM is A[m x K] @ B[K x N] (Table 1 caption):
@@ -93,7 +100,7 @@ int moe_quantize_experts(const float *w, int E, int K, int N, int bits, int grou
  *   x [T,d] act_dtype (MOE_F16 | MOE_BF16), wg [d,E] same dtype, bias [E] fp32 or NULL
  *   finished [T] bytes (device) or NULL (no row is pruned)
  *   expert_idx [T,k] int32, expert_scale [T,k] fp32
- * Requires 1 <= k <= 2, k <= E <= 256, d >= 1.
+ * Requires 1 <= k <= 2, k <= E <= 256, d >= 8 and d % 8 == 0.
  */
 int moe_gate_topk(const void *x, int act_dtype, const void *wg, const float *bias,
                   const uint8_t *finished, int T, int d, int E, int k, int renormalize,

@@ -200,8 +200,8 @@ void orc_int4_interleave8(const int8_t *in /*[8]*/, int8_t *out /*[8]*/)
 
 /* ---------------------------------------------------------------- gating (Sec. 3.3)
  * logit[t,e] = sum_i x[t,i] * wg[i,e] + bias[e]; the k largest logits win (ties: lower
- * expert index; slot order: descending logit).  The paper only says "top-k gating function
- * outputs (expert_scale, expert_idx)" and names Switch top-1 gating, so: softmax over all E
+ * expert index; slot order: descending logit).  Sec. 3.3 defines the gate only as returning k
+ * (scale, index) tuples per token, and Sec. 3.1 names Switch top-1 gating, so: softmax over all E
  * logits, scale = probability of the chosen expert; for k > 1 with `renorm` the k
  * probabilities are divided by their sum.
  *

@@ -24,6 +24,8 @@ EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gat
            "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed",
            "moe_grouped_ffn_wq_gated_supported", "moe_grouped_ffn_wq_gated"]
 
+LAYER_MAX_EXPERTS = 256   # experts of a whole layer call: moe_gate_topk's limit (moe_permute: 1024, the FFN: 4096)
+
 _lib = None
 ACTIVATIONS = {"relu": 0, "gelu": 1}     # MOE_ACT_RELU, MOE_ACT_GELU
 

@@ -11,6 +11,12 @@ from . import binding as B
 class MoEExpertLayer:
     def __init__(self, T, d, F, E, k, bits, group_size=0, act_dtype=torch.float16, renormalize=True,
                  y_dtype=None, out_dtype=torch.float32, device="cuda:0", fuse_routing=True, activation="relu"):
+        # what a whole layer call takes (the gate's limits are the narrowest of the entry points')
+        if not (1 <= k <= 2 and k <= E <= B.LAYER_MAX_EXPERTS):
+            raise B.MoeError("a layer call takes k = 1 or 2 experts per token and k <= E <= %d experts (k=%d E=%d)"
+                             % (B.LAYER_MAX_EXPERTS, k, E))
+        if T < 0 or d <= 0 or F <= 0 or d % 64 or F % 64:
+            raise B.MoeError("a layer call takes T >= 0 and d, F positive multiples of 64 (T=%d d=%d F=%d)" % (T, d, F))
         self.T, self.d, self.F, self.E, self.k = T, d, F, E, k
         self.bits, self.group_size, self.renormalize = bits, group_size, renormalize
         self.act_dtype, self.out_dtype = act_dtype, out_dtype

@@ -105,3 +105,22 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(binding.MoeError):
         binding.load()
+
+
+def test_layer_level_limits_are_checked_before_anything_is_allocated(lib):
+    """A whole layer call takes what its narrowest entry point takes: the gate's E <= 256 and k <= 2
+    (moe_permute alone goes to 1024 experts and the FFN to 4096), and the FFN's d, F multiples of 64."""
+    from paper_2211_10017_amd import MoEExpertLayer
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)          # never dereferenced: validation fails first
+    most = binding.LAYER_MAX_EXPERTS
+    assert lib.moe_gate_topk(fake, 0, fake, None, None, 4, 64, most + 1, 1, 1, fake, fake, None) == 2
+    assert b"above %d" % most in lib.moe_last_error()
+    header = open(os.path.join(ROOT, "include", "moe_wq.h")).read()
+    assert "k <= E <= %d" % most in header                      # the header's preamble states the same number
+    for bad in (dict(E=most + 1, k=1), dict(E=8, k=3), dict(E=1, k=2), dict(E=8, k=0)):
+        with pytest.raises(binding.MoeError, match="layer call"):
+            MoEExpertLayer(16, 64, 128, bad["E"], bad["k"], 4, device="cpu")
+    for d, F in ((96, 128), (64, 100), (0, 128)):
+        with pytest.raises(binding.MoeError, match="multiples of 64"):
+            MoEExpertLayer(16, d, F, 8, 1, 4, device="cpu")

@@ -1,8 +1,9 @@
 """GPU parity at the five benchmark configurations (full sizes, the launch configuration
 bench.py times): quantiser bytes, routing indices and permutation bit-exact; layer output
 within max-abs 2e-2 and relative L2 1e-3 of the oracle run on the same quantised weights.
-Where the oracle cannot finish the whole output in seconds it computes a seeded sample of
-tokens (exact for those rows, since rows are independent given the routing)."""
+Where the oracle cannot finish the whole output in seconds it computes a sample of at least
+1024 tokens (exact for those rows, since rows are independent given the routing) that holds
+the first and last row of every 32-row run of every expert, so every row tile is sampled."""
 import gc
 
 import numpy as np
@@ -24,6 +25,24 @@ pytestmark = pytest.mark.gpu
 
 def _say(msg):
     print(msg, flush=True)
+
+
+def _structured_tokens(perm_src, off, k, E, T, at_least, seed):
+    """Tokens for a sampled comparison that leaves no row tile of any expert unchecked: for every
+    expert the first and the last row of each run of 32 rows (the height of one matrix instruction,
+    which every row-tile height the kernels use is a multiple of) and the expert's last row, topped
+    up with seeded random tokens to `at_least`.  A token is checked with all k of its rows."""
+    rows = []
+    for e in range(E):
+        lo, hi = int(off[e]), int(off[e + 1])
+        for r0 in range(lo, hi, 32):
+            rows += [r0, min(r0 + 31, hi - 1)]
+        if hi > lo:
+            rows.append(hi - 1)
+    tokens = set((perm_src[np.asarray(sorted(set(rows)), dtype=np.int64)] // k).tolist())
+    rest = [t for t in np.random.default_rng(seed).permutation(T).tolist() if t not in tokens]
+    tokens.update(rest[:max(0, at_least - len(tokens))])
+    return np.asarray(sorted(tokens), dtype=np.int64)
 
 
 def _check_layer(prep, sample_tokens):
@@ -53,12 +72,12 @@ def _check_layer(prep, sample_tokens):
     if sample_tokens is None or sample_tokens >= w.T:
         tokens = np.arange(w.T)
     else:
-        tokens = np.random.default_rng(w.seed).choice(w.T, size=sample_tokens, replace=False)
+        tokens = _structured_tokens(perm_src, off, w.k, w.E, w.T, sample_tokens, w.seed)
     # with one expert per token a routed layer scales and stores fc2's fp32 result directly: y is never rounded
     y_dt = torch.float32 if (layer.routed and w.k == 1) or _adds_into_out(layer) else layer.y_dtype
     tokens, want = prep.oracle_out_for_tokens(tokens, idx, scale, perm_src, inv_perm, off, oracle_dtype_code(y_dt))
     max_abs, rel = error_metrics(got[tokens], want)
-    _say(f"   {w.name}: tokens checked {len(tokens)}  max_abs={max_abs:.3e}  rel_l2={rel:.3e}")
+    _say(f"   {w.name}: tokens checked {len(tokens)} of {w.T}  max_abs={max_abs:.3e}  rel_l2={rel:.3e}")
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
     # properties that hold at any size: a second call is bit-identical; outputs are not trivially zero
     out2 = layer.forward(prep.x_dev).clone()
@@ -67,7 +86,7 @@ def _check_layer(prep, sample_tokens):
     assert float(np.abs(got).mean()) > 1e-3
 
 
-@pytest.mark.parametrize("name,sample", [("c1", None), ("c2", None), ("c3", 2048), ("c4", 512)])
+@pytest.mark.parametrize("name,sample", [("c1", None), ("c2", None), ("c3", 2048), ("c4", 1024)])
 def test_config(name, sample):
     _say(f"config {name}")
     prep = Prepared(W.WORKLOADS[name])
@@ -119,7 +138,7 @@ def test_config_with_pruned_rows(name):
 def test_config_c5_fp16_then_bf16():
     _say("config c5 fp16")
     prep = Prepared(W.WORKLOADS["c5"])
-    _check_layer(prep, 96)
+    _check_layer(prep, 1024)
     _say("config c5 bf16 (same weights)")
     wb = W.WORKLOADS["c5_bf16"]
     prep.w = wb
@@ -131,7 +150,7 @@ def test_config_c5_fp16_then_bf16():
     prep.layer.wg.copy_(to_dev(prep.wg, torch.bfloat16))
     prep.x_dev = to_dev(prep.x, torch.bfloat16)
     del old
-    _check_layer(prep, 96)
+    _check_layer(prep, 1024)
     del prep
     gc.collect()
     torch.cuda.empty_cache()

@@ -178,6 +178,12 @@ def _ffn_case(rows_per_expert, d, F, bits, g, act, y_dt, seed, with_bias=False, 
     ([300, 280], 2112, 2176, 8, 64, "f16", torch.float32),
     ([290, 300], 2112, 2112, 8, 0, "bf16", torch.float32),
     ([150, 120], 2112, 2112, 4, 64, "bf16", torch.float32),         # two-term group scales in 128-row tiles
+    # 4-bit weights, group scales, fp16 rows, K above 2048 in both GEMMs, more than 64 rows per expert on
+    # average: the 128-row tiles with a scale per group (the variant the largest workload's fp16 pass runs),
+    # every row compared; rows dealt 96+96+78, 96+96+65 and 96+34
+    ([270, 257, 130], 2112, 2176, 4, 64, "f16", torch.float16),
+    ([270, 257, 130], 2176, 2304, 4, 128, "f16", torch.float32),
+    ([129, 288, 1, 256], 2304, 2176, 4, 128, "f16", torch.float16), # 128 + 1 rows; nine 32-row units in three tiles; one row; two full tiles
 ])
 def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     _say(f"ffn rows={rows} d={d} F={F} bits={bits} g={g} {act} y={y_dt}")
@@ -354,10 +360,15 @@ def test_grouped_gemm_matches_oracle(bits, native, K, N):
 
 
 # ------------------------------------------------------------------ routing fused into the GEMMs
-@pytest.mark.parametrize("T,k,E,d,F,bits,g", [(700, 1, 5, 128, 256, 4, 0), (300, 2, 3, 192, 320, 8, 0),
-                                               (1500, 1, 4, 256, 512, 4, 128)])
-def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g):
-    _say(f"routed ffn T={T} k={k} E={E} d={d} F={F} bits={bits} g={g}")
+@pytest.mark.parametrize("T,k,E,d,F,bits,g,o_dt", [
+    (700, 1, 5, 128, 256, 4, 0, torch.float32), (300, 2, 3, 192, 320, 8, 0, torch.float32),
+    (1500, 1, 4, 256, 512, 4, 128, torch.float32),
+    # the fused un-permute storing 16-bit layer outputs
+    (700, 1, 5, 128, 256, 4, 0, torch.float16), (650, 1, 3, 192, 320, 8, 0, torch.bfloat16),
+    # rows fetched through the routing index by the 128-row tiles with a scale per group (K above 2048, 4-bit)
+    (700, 1, 3, 2176, 2304, 4, 128, torch.float32), (400, 2, 3, 2112, 2176, 4, 64, torch.float32)])
+def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g, o_dt):
+    _say(f"routed ffn T={T} k={k} E={E} d={d} F={F} bits={bits} g={g} out={o_dt}")
     rng = np.random.default_rng(T + E + bits)
     x = rng.standard_normal((T, d)).astype(np.float16).astype(np.float32)
     wg = (rng.standard_normal((d, E)) * 0.05).astype(np.float16).astype(np.float32)
@@ -385,14 +396,18 @@ def test_routed_ffn_matches_oracle(T, k, E, d, F, bits, g):
     assert np.array_equal(ps.cpu().numpy(), res["perm_src"]) and np.array_equal(of.cpu().numpy(), res["expert_offsets"])
     if k == 1:      # gather and un-permute + scale fused: the call returns the layer output
         out = B.moe_grouped_ffn_wq_routed(xd, ps, k, of, E, d, F, bits, g, p1, ds1, p2, ds2, expert_scale=scale.view(-1),
-                                          out_dtype=torch.float32)
+                                          out_dtype=o_dt)
     else:           # gather fused; combine as usual
         y = B.moe_grouped_ffn_wq_routed(xd, ps, k, of, E, d, F, bits, g, p1, ds1, p2, ds2, out_dtype=torch.float32)
-        out = B.moe_combine(y, ip, scale, T, k)
+        out = B.moe_combine(y, ip, scale, T, k, out_dtype=o_dt)
     torch.cuda.synchronize()
-    max_abs, rel = error_metrics(out.cpu().numpy(), res["out"])
+    assert out.dtype == o_dt
+    want = oracle.round_to(res["out"], oracle_dtype_code(o_dt))     # the layer output stored in o_dt: one rounding of the fp32 result
+    max_abs, rel = error_metrics(out.float().cpu().numpy(), want)
     _say(f"   max_abs={max_abs:.3e} rel_l2={rel:.3e}")
-    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+    # a 16-bit output that lands on the other side of a rounding boundary differs by one unit in the last place
+    ulp = {torch.float32: 0.0, torch.float16: 2.0 ** -10, torch.bfloat16: 2.0 ** -7}[o_dt] * float(np.abs(want).max())
+    assert max_abs <= MAX_ABS_TOL + ulp and rel <= REL_L2_TOL + (1e-3 if o_dt == torch.bfloat16 else 0.0)
 
 
 @pytest.mark.parametrize("T,k,E,d,F,bits,prune", [(64, 2, 32, 1024, 4096, 4, 0),     # the decode workload's shape
