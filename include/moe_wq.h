@@ -164,6 +164,28 @@ int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_
                        size_t workspace_bytes, void *stream);
 
 /*
+ * moe_grouped_ffn_wq for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and same results (bit for bit: the same kernels run) as moe_grouped_ffn_wq without the
+ * workspace pair; h (and the per-row factors of bf16 rows) live in a fixed array of
+ * moe_grouped_ffn_wq_noalloc_max_bytes() = 8 MiB inside the library's own device memory, which
+ * every GPU the library is used on holds until the process ends.  The call allocates and frees
+ * nothing (its first call on a device looks up the array's address, nothing more).
+ *   Sizes whose moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype) exceeds the array are
+ *   refused with MOE_ERR_WORKSPACE before anything is launched (decode-sized batches fit: 128 rows
+ *   of F = 4096 take 1 MiB; R * F <= 4 Mi elements of fp16 in general).
+ *   All calls on one GPU share that GPU's array, which keeps the last call's h: nothing in it has
+ *   to start from zero (fc1 writes every row fc2 reads), but two calls that overlap in time on one
+ *   GPU (different streams or host threads) race on it.  Calls on one stream are safe.
+ */
+size_t moe_grouped_ffn_wq_noalloc_max_bytes(void);
+int moe_grouped_ffn_wq_noalloc(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
+                               int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                               int activation, const void *w1_packed,
+                               const void *s1, const void *b1, const void *w2_packed, const void *s2,
+                               const void *b2, void *y_perm, int y_dtype, void *stream);
+
+/*
  * moe_grouped_ffn_wq with the routing fused into the GEMMs, for batches large enough to run in
  * the tiled kernel: fc1 fetches row r from x[perm_src[r] / k] (no x_perm copy is needed:
  * moe_permute may be called with x = x_perm = NULL), and, when expert_scale is given (k = 1

@@ -22,7 +22,8 @@ EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gat
            "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
            "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq",
            "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed",
-           "moe_grouped_ffn_wq_gated_supported", "moe_grouped_ffn_wq_gated"]
+           "moe_grouped_ffn_wq_gated_supported", "moe_grouped_ffn_wq_gated",
+           "moe_grouped_ffn_wq_noalloc_max_bytes", "moe_grouped_ffn_wq_noalloc"]
 
 LAYER_MAX_EXPERTS = 256   # experts of a whole layer call: moe_gate_topk's limit (moe_permute: 1024, the FFN: 4096)
 
@@ -59,6 +60,10 @@ def load():
     lib.moe_grouped_ffn_wq_workspace_bytes.argtypes = [i, i, i, i, i]
     lib.moe_grouped_ffn_wq.restype = i
     lib.moe_grouped_ffn_wq.argtypes = [vp, i, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp, sz, vp]
+    lib.moe_grouped_ffn_wq_noalloc_max_bytes.restype = sz
+    lib.moe_grouped_ffn_wq_noalloc_max_bytes.argtypes = []
+    lib.moe_grouped_ffn_wq_noalloc.restype = i
+    lib.moe_grouped_ffn_wq_noalloc.argtypes = [vp, i, vp, i, i, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, i, vp]
     lib.moe_grouped_ffn_wq_routed_supported.restype = i
     lib.moe_grouped_ffn_wq_routed_supported.argtypes = [i, i, i, i, i, i, i, i]
     lib.moe_grouped_ffn_wq_routed.restype = i
@@ -190,6 +195,22 @@ def moe_grouped_ffn_wq(x_perm, expert_offsets, E: int, d: int, F: int, bits: int
         _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"), _ptr(b2, torch.float16, "b2"),
         _ptr(y_perm), _DT[y_perm.dtype], _ptr(workspace), workspace.numel(), _stream())
     _check(rc, "moe_grouped_ffn_wq")
+    return y_perm
+
+
+def moe_grouped_ffn_wq_noalloc(x_perm, expert_offsets, E: int, d: int, F: int, bits: int, group_size: int,
+                               w1_packed, s1, w2_packed, s2, y_perm, b1=None, b2=None,
+                               max_rows_per_expert: int = 0, activation: str = "relu"):
+    """moe_grouped_ffn_wq without a workspace (scratch inside the library); y_perm is the caller's."""
+    R = x_perm.shape[0]
+    rc = load().moe_grouped_ffn_wq_noalloc(
+        _ptr(x_perm, (torch.float16, torch.bfloat16), "x_perm"), _DT[x_perm.dtype],
+        _ptr(expert_offsets, torch.int32, "expert_offsets"), R, E, max_rows_per_expert, d, F, bits, group_size,
+        ACTIVATIONS[activation],
+        _ptr(w1_packed, torch.uint8, "w1_packed"), _ptr(s1, torch.float16, "s1"), _ptr(b1, torch.float16, "b1"),
+        _ptr(w2_packed, torch.uint8, "w2_packed"), _ptr(s2, torch.float16, "s2"), _ptr(b2, torch.float16, "b2"),
+        _ptr(y_perm), _DT[y_perm.dtype], _stream())
+    _check(rc, "moe_grouped_ffn_wq_noalloc")
     return y_perm
 
 

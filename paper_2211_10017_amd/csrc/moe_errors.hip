@@ -29,4 +29,4 @@ int check_launch(const char *what)
 }  // namespace moe
 
 extern "C" const char *moe_last_error(void) { return moe::error_buffer(); }
-extern "C" int moe_abi_version(void) { return 3; }
+extern "C" int moe_abi_version(void) { return 4; }

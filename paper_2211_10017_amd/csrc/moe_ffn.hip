@@ -3,6 +3,8 @@
 // argument checks, workspace layout and the choice between the weight-streaming kernel
 // (experts with few rows, HBM-bound) and the LDS-tiled kernel (experts with many rows,
 // MFMA-bound).
+#include <mutex>
+
 #include "moe_ffn_common.h"
 
 namespace moe {
@@ -207,6 +209,61 @@ extern "C" int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32
 {
     return ffn_impl(x_perm, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, activation, w1_packed,
                     s1, b1, w2_packed, s2, b2, y_perm, y_dtype, workspace, workspace_bytes, stream, nullptr, 1, nullptr);
+}
+
+// ---- the entry point for callers that cannot allocate ------------------------------------------
+// moe_grouped_ffn_wq with its workspace (h, and for bf16 rows the per-row factors) in a fixed array in
+// the library's own device memory.  Every GPU the library runs on holds its own copy of the array
+// until the process ends.
+constexpr size_t kScratchBytes = (size_t)8 << 20;
+constexpr int kScratchMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// Device address of `scratch` on the current device, looked up once per device (0 on failure, with
+// the error message set).  In host code the array's name is only a handle for this lookup.
+static void *scratch_address()
+{
+    using namespace moe;
+    static std::mutex lock;
+    static void *address[kScratchMaxDevices];           // zero-initialised: not looked up yet
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess || dev < 0 || dev >= kScratchMaxDevices) {
+        fail(MOE_ERR_HIP, "moe_grouped_ffn_wq_noalloc: no current device (%s)", hipGetErrorString(err));
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !ptr) {
+            fail(MOE_ERR_HIP, "moe_grouped_ffn_wq_noalloc: hipGetSymbolAddress failed on device %d (%s)", dev, hipGetErrorString(err));
+            return nullptr;
+        }
+        address[dev] = ptr;
+    }
+    return address[dev];
+}
+
+extern "C" size_t moe_grouped_ffn_wq_noalloc_max_bytes(void) { return kScratchBytes; }
+
+extern "C" int moe_grouped_ffn_wq_noalloc(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
+                                          int E, int max_rows_per_expert, int d, int F, int bits, int group_size,
+                                          int activation, const void *w1_packed,
+                                          const void *s1, const void *b1, const void *w2_packed, const void *s2,
+                                          const void *b2, void *y_perm, int y_dtype, void *stream)
+{
+    using namespace moe;
+    if (R > 0 && d > 0 && F > 0) {
+        const size_t need = moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype);
+        if (need > kScratchBytes)
+            return fail(MOE_ERR_WORKSPACE, "moe_grouped_ffn_wq_noalloc: R=%d rows of F=%d need %zu bytes of scratch, the built-in "
+                                           "array holds %zu: use moe_grouped_ffn_wq with a workspace", R, F, need, kScratchBytes);
+    }
+    void *ws = scratch_address();
+    if (!ws) return MOE_ERR_HIP;
+    return ffn_impl(x_perm, act_dtype, expert_offsets, R, E, max_rows_per_expert, d, F, bits, group_size, activation, w1_packed,
+                    s1, b1, w2_packed, s2, b2, y_perm, y_dtype, ws, kScratchBytes, stream, nullptr, 1, nullptr);
 }
 
 // The same pair of GEMMs with the row gather (and, for k = 1, the un-permute and gate scale) fused

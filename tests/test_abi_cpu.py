@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.moe_abi_version() == 3
+    assert lib.moe_abi_version() == 4
 
 
 def test_workspace_queries_are_host_functions(lib):
