@@ -59,6 +59,14 @@ enum { MOE_ACT_RELU = 0, MOE_ACT_GELU = 1 };
 /* Message for the last error returned on this thread ("" if none). */
 const char *moe_last_error(void);
 
+/* Names of the GEMM kernels that the last moe_grouped_ffn_wq* call on this thread launched, fc1
+ * first, separated by a blank ("" before the first call); for measurement reports. */
+const char *moe_last_ffn_kernels(void);
+
+/* What the current device reports (HOST pointers, any may be NULL): compute units, engine and
+ * memory clock in kHz, memory bus width in bits; for reports that re-derive the chip's peaks. */
+int moe_device_info(int *compute_units, int *engine_clock_khz, int *memory_clock_khz, int *memory_bus_bits);
+
 /* Library ABI version (bumped when a signature or the packed layout changes). */
 int moe_abi_version(void);
 

@@ -65,6 +65,11 @@ def num_threads() -> int:
     return int(_c().orc_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads the oracle's loops use from now on (for timing it on one core)."""
+    _c().orc_set_num_threads(ctypes.c_int(int(n)))
+
+
 # ------------------------------------------------------------------ number formats
 def f32_to_f16_bits(v: float) -> int:
     return int(_c().orc_f32_to_f16_bits(ctypes.c_float(v)))

@@ -357,3 +357,14 @@ int orc_num_threads(void)
 #endif
     return n;
 }
+
+/* Threads the parallel loops above use from now on (n >= 1); for timing the oracle on one core.
+ * Not part of any computation. */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

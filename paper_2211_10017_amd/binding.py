@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_wq.so")
 MOE_F16, MOE_BF16, MOE_F32 = 0, 1, 2
 _DT = {torch.float16: MOE_F16, torch.bfloat16: MOE_BF16, torch.float32: MOE_F32}
 
-EXPORTS = ["moe_last_error", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
+EXPORTS = ["moe_last_error", "moe_last_ffn_kernels", "moe_device_info", "moe_abi_version", "moe_quantize_experts", "moe_gate_topk",
            "moe_permute_workspace_bytes", "moe_permute", "moe_grouped_ffn_wq_workspace_bytes",
            "moe_grouped_ffn_wq", "moe_combine", "moe_pack_fp16_experts", "moe_grouped_gemm_wq",
            "moe_grouped_ffn_wq_routed_supported", "moe_grouped_ffn_wq_routed",
@@ -47,6 +47,10 @@ def load():
     vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.moe_last_error.restype = ctypes.c_char_p
     lib.moe_last_error.argtypes = []
+    lib.moe_last_ffn_kernels.restype = ctypes.c_char_p
+    lib.moe_last_ffn_kernels.argtypes = []
+    lib.moe_device_info.restype = i
+    lib.moe_device_info.argtypes = [ctypes.POINTER(i)] * 4
     lib.moe_abi_version.restype = i
     lib.moe_quantize_experts.restype = i
     lib.moe_quantize_experts.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp]
@@ -82,6 +86,13 @@ def load():
     lib.moe_combine.argtypes = [vp, i, vp, vp, vp, i, i, i, vp, i, vp]
     _lib = lib
     return lib
+
+
+def moe_device_info() -> dict:
+    """Compute units, engine / memory clock (kHz) and memory bus width (bits) of the current device."""
+    v = [ctypes.c_int(0) for _ in range(4)]
+    _check(load().moe_device_info(*[ctypes.byref(x) for x in v]), "moe_device_info")
+    return dict(zip(("compute_units", "engine_clock_khz", "memory_clock_khz", "memory_bus_bits"), (x.value for x in v)))
 
 
 def _check(rc: int, what: str):

@@ -16,6 +16,8 @@ constexpr int kWave = 64;
 char *error_buffer();
 int fail(int code, const char *fmt, ...);
 int check_launch(const char *what);
+void reset_kernel_notes();
+void note_kernel(const char *name);
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

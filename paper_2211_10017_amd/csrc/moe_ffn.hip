@@ -97,6 +97,7 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
 {
     using namespace moe;
     const GemmKernel kernel = choose_kernel(g.R, g.E, max_rows, g.K, g.N, bits, smode, bf);
+    note_kernel(kernel == GEMM_STREAM_UNROLLED ? "stream_unrolled_kernel" : kernel == GEMM_STREAM_LOOP ? "stream_gemm_kernel" : "grouped_gemm_kernel");
     if (kernel == GEMM_STREAM_UNROLLED) return launch_stream_unrolled(g, bits, max_rows, s);
     if (g.gate_idx || g.out_add) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq_gated: K=%d does not run in the straight-line kernel with these sizes", g.K);
     if (kernel == GEMM_STREAM_LOOP) return launch_stream_gemm(g, bits, smode, max_rows, s);
@@ -145,6 +146,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     const FfnWorkspace ws = ffn_workspace(R, d, F, act_dtype);
     if (!workspace || workspace_bytes < ws.total)
         return fail(MOE_ERR_WORKSPACE, "moe_grouped_ffn_wq: workspace of %zu bytes needed, %zu given", ws.total, workspace_bytes);
+    reset_kernel_notes();
     if (R == 0) return MOE_OK;
 
     hipStream_t s = as_stream(stream);
