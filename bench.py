@@ -156,17 +156,19 @@ def measure(name, args, cpu_baseline, headline):
     tokens_per_s = w.T * steps / elapsed
     kernels = binding.load().moe_last_ffn_kernels().decode()      # what the library launched for the GEMM pair
 
-    # ---- the same K steps again with HIP events around the grouped-GEMM launches (events are on
-    # torch's current stream, which is the stream the library launches on): the roofline's timing
-    evf = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-    for i in range(steps):
-        layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
-        layer.gate(x, finished)
-        layer.permute(x, finished)
-        evf[i][0].record()
-        layer.ffn(x, finished)
-        evf[i][1].record()
-        layer.combine(x, finished)
+    # ---- the grouped FFN alone, K calls back to back between two HIP events (on torch's current stream,
+    # which is the stream the library launches on): the roofline's timing.  Routing state is that of
+    # the last step; every call streams another ring copy of the weights.  Event pairs around single
+    # calls would add the events' own cost (several microseconds, see step_us.empty_interval) to a
+    # call that takes tens of microseconds.
+    reps = 5
+    evf = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evf:
+        a.record()
+        for i in range(steps):
+            layer.w1_packed, layer.s1, layer.w2_packed, layer.s2 = ring[i % ncopy]
+            layer.ffn(x, finished)
+        b.record()
     torch.cuda.synchronize()
     # ---- and once more with an event between all steps of the path: median and minimum of each step
     names = ["gate", "permute", "ffn", "combine"]
@@ -195,8 +197,10 @@ def measure(name, args, cpu_baseline, headline):
     per_step["empty_interval"] = stats_us([a.elapsed_time(b) for a, b in idle])
     planned = [what for _, _, what in layer._plan(x, finished)]
     per_step["launch_sequence"] = planned            # a step the fused entry points absorbed shows ~0 us above
-    ffn_ms = np.array([a.elapsed_time(b) for a, b in evf])
-    launches_per_ffn = 2                       # fc1 and fc2 are two launches of the GEMM kernel
+    ffn_ms = np.array([a.elapsed_time(b) / steps for a, b in evf])     # per call, each averaged over K calls
+    # fc1 and fc2 are two launches of the GEMM kernel, except in the decode kernel, which streams both
+    # weight matrices in one launch (its small slice reduction is counted into the same interval)
+    launches_per_ffn = max(1, len(kernels.split()))
     launch_s = float(ffn_ms.mean()) * 1e-3 / launches_per_ffn
 
     if args.traffic_calibration:
@@ -227,8 +231,9 @@ def measure(name, args, cpu_baseline, headline):
     roofline["traffic"] = traffic
     roofline.update({"traffic_source": source, "kernel": kernels.split()[0] if kernels else None, "kernels_launched": kernels,
                      "launches_per_step": launches_per_ffn,
-                     "avg_launch_us": launch_s * 1e6, "ffn_us_median": float(np.median(ffn_ms)) * 1e3,
-                     "ffn_us_min": float(ffn_ms.min()) * 1e3, "active_experts": active,
+                     "avg_launch_us": launch_s * 1e6, "ffn_call_us_mean": float(ffn_ms.mean()) * 1e3,
+                     "ffn_call_us_min": float(ffn_ms.min()) * 1e3, "timing": "%d x %d back-to-back FFN calls between HIP events" % (reps, steps),
+                     "active_experts": active,
                      "algorithmic_bytes_per_step": int(bytes_ffn), "flops_per_step": flops_ffn,
                      "weight_ring_copies": ncopy})
 

@@ -162,6 +162,8 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  *   y_perm [R,d] in y_dtype (MOE_F16 | MOE_BF16 | MOE_F32)
  * Requires d % 64 == 0, F % 64 == 0, bits in {4,8}, group_size 0 or a multiple of 64 dividing
  * both d and F.
+ * Workspace: h (R * F elements of act_dtype), the per-row factors of bf16 rows, and for decode-sized
+ * batches (R <= 256) the partial sums moe_grouped_ffn_wq_gated keeps (F / 512 x R x d fp32).
  */
 size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E, int act_dtype);
 int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
@@ -232,6 +234,13 @@ int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_
  *   expert_scale[a] * y[row of a] into row a / k with hardware fp32 adds.  A token gets at
  *   most two terms and fp32 addition of two terms onto zero is commutative, so the result
  *   does not depend on the order of arrival; rows of pruned tokens stay zero.
+ *   With expert_scale given and sizes the decode kernel is built for (4-bit: d = 1024; 8-bit:
+ *   d = 512; F a multiple of 512 up to 4096; at most 8 assignments per expert on average and at
+ *   least 64 slices of 512 d_ff channels in all), the call is two launches: a persistent grid of one
+ *   workgroup per compute unit streams every active expert's W1 and W2 once (fc1, activation and
+ *   fc2 per 512-channel slice of d_ff, h staying on chip) and leaves fp32 partial sums of y in the
+ *   workspace; a small second launch adds the slices in a fixed order, applies the channel scale,
+ *   bias and gate scale and writes out.  No atomics on this path.
  * moe_grouped_ffn_wq_gated_supported returns 0 when a call with these sizes is not taken
  * (it then returns MOE_ERR_UNSUPPORTED and launches nothing), 1 when it is taken with
  * expert_scale = NULL, 2 when expert_scale may be given too.  Taken: fp16 activations,

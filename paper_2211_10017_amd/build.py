@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libmoe_wq.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["moe_errors.hip", "moe_quantize.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip", "moe_ffn_tiled.hip", "moe_ffn_tiled_4_f16.hip", "moe_ffn_tiled_4_bf16.hip",
-           "moe_ffn_tiled_8_f16.hip", "moe_ffn_tiled_8_bf16.hip", "moe_ffn_stream.hip",
+           "moe_ffn_tiled_8_f16.hip", "moe_ffn_tiled_8_bf16.hip", "moe_ffn_stream.hip", "moe_ffn_decode.hip",
            "moe_combine.hip"]
 
 # packed-fp32 VALU forms are switched off for every translation unit of this library

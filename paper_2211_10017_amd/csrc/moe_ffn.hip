@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void row_pow_kernel(const uint16_t *__restrict
 }
 
 struct FfnWorkspace {
-    size_t h_off, pow_x_off, pow_h_off, total;
+    size_t h_off, pow_x_off, pow_h_off, partial_off, total;
 };
 
 static FfnWorkspace ffn_workspace(int R, int d, int F, int act_dtype)
@@ -54,6 +54,8 @@ static FfnWorkspace ffn_workspace(int R, int d, int F, int act_dtype)
     if (act_dtype == MOE_BF16) o += round_up((size_t)R * sizeof(float2), 256);
     w.pow_h_off = o;
     if (act_dtype == MOE_BF16) o += round_up((size_t)R * sizeof(float2), 256);
+    w.partial_off = o;                           // decode kernel: partial sums of y per d_ff slice
+    if (R <= kGatedMaxAssign && F % 512 == 0) o += round_up(decode_ffn_partial_bytes(R, d, F), 256);
     w.total = o < 256 ? 256 : o;
     return w;
 }
@@ -154,6 +156,18 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     const int max_rows = max_rows_per_expert > 0 && max_rows_per_expert < R ? max_rows_per_expert : R;
     unsigned char *wsb = (unsigned char *)workspace;
     void *h = wsb + ws.h_off;
+    // decode-sized batch with everything fused: one streaming launch for the sort and both GEMMs, then the slice reduction
+    if (gate_idx && expert_scale && !bf && group_size == 0 && decode_ffn_supports(R, E, d, F, bits)) {
+        DecodeArgs q{};
+        q.x = (const uint16_t *)x_perm; q.gate_idx = gate_idx; q.gate_scale = expert_scale; q.n_assign = R; q.gate_k = k;
+        q.E = E; q.d = d; q.F = F; q.act = activation;
+        q.w1 = (const uint8_t *)w1_packed; q.w2 = (const uint8_t *)w2_packed;
+        q.s1 = (const __half *)s1; q.s2 = (const __half *)s2; q.b1 = (const __half *)b1; q.b2 = (const __half *)b2;
+        q.partial = (float *)(wsb + ws.partial_off); q.out = (float *)y_perm;
+        q.perm_src_out = perm_src_out; q.inv_perm_out = inv_perm_out; q.offsets_out = offsets_out;
+        note_kernel("decode_ffn_kernel");
+        return launch_decode_ffn(q, bits, as_stream(stream));
+    }
     float2 *pow_x = (float2 *)(wsb + ws.pow_x_off), *pow_h = (float2 *)(wsb + ws.pow_h_off);
     const bool grouped = group_size != 0 && !(group_size == d && group_size == F);
 

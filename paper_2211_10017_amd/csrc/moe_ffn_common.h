@@ -44,6 +44,26 @@ struct GemmArgs {
     int out_add, out_div;
 };
 
+// FFN of a decode-sized batch: one streaming launch plus a small reduction (moe_ffn_decode.hip).
+struct DecodeArgs {
+    const uint16_t *x;          // [T, d] fp16, un-permuted
+    const int32_t *gate_idx;    // [n_assign] expert of assignment a (E = pruned row)
+    const float *gate_scale;    // [n_assign] gate scale of assignment a
+    int n_assign, gate_k;
+    int E, d, F, act;
+    const uint8_t *w1, *w2;     // packed codes
+    const __half *s1, *s2;      // per-channel scales [E, F] / [E, d]
+    const __half *b1, *b2;      // biases or null
+    float *partial;             // [F / 512, n_assign, d] fp32: y summed over one 512-channel slice of d_ff
+    float *out;                 // [T, d] fp32 layer output
+    int32_t *perm_src_out, *inv_perm_out, *offsets_out;
+    int items1;                 // workgroup items (set by the launcher)
+};
+constexpr int kDecMaxExperts = 4096;
+bool decode_ffn_supports(int n_assign, int E, int d, int F, int bits);
+size_t decode_ffn_partial_bytes(int n_assign, int d, int F);
+int launch_decode_ffn(const DecodeArgs &p, int bits, hipStream_t s);
+
 constexpr int kGatedMaxAssign = 256;    // assignments the fused permutation takes: one per thread of a block
 
 int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);

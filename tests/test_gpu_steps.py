@@ -463,6 +463,77 @@ def test_gated_ffn_matches_oracle(T, k, E, d, F, bits, prune):
         assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
 
+def _routing(kind, T, k, E, rng):
+    """Expert indices [T, k] (distinct per token) for the decode-kernel cases."""
+    idx = np.empty((T, k), dtype=np.int32)
+    for t in range(T):
+        if kind == "uniform":
+            idx[t] = rng.choice(E, size=k, replace=False)
+        elif kind == "one_hot_expert":          # expert 3 takes a row of every token: several passes of sixteen rows
+            others = [e for e in range(E) if e != 3]
+            idx[t] = ([3] + list(rng.choice(others, size=k - 1, replace=False)))[:k]
+            if k == 2 and t % 2:
+                idx[t] = idx[t][::-1]
+        elif kind == "few_experts":             # most experts stay empty
+            idx[t] = rng.choice(5, size=k, replace=False) * 3
+    return idx
+
+
+@pytest.mark.parametrize("T,k,E,d,F,bits,kind,extras", [
+    (64, 2, 32, 1024, 4096, 4, "uniform", ""),                  # the decode workload's shape
+    (64, 2, 32, 1024, 4096, 4, "one_hot_expert", ""),           # 64 rows in one expert: four passes; the rest one or two rows
+    (30, 2, 32, 1024, 4096, 4, "few_experts", "pruned"),        # 27 experts without rows, pruned tokens
+    (64, 2, 32, 512, 2048, 8, "uniform", "bias gelu"),          # 8-bit weights, biases, GELU
+    (1, 1, 64, 1024, 1024, 4, "uniform", ""),                   # a single row
+    (128, 2, 136, 1024, 1024, 4, "uniform", ""),                # 272 items: some workgroups take two
+    (50, 1, 16, 1024, 2048, 4, "one_hot_expert", "bias")])      # one expert per token, all fifty rows in one expert
+def test_decode_ffn_matches_oracle(T, k, E, d, F, bits, kind, extras):
+    """Decode-sized batches with the gate scale fused in: one streaming launch (sort, fc1, activation, fc2 per
+    slice of d_ff) and the slice reduction.  Index arrays bit-exact, output within the layer tolerance, two
+    calls bit-identical."""
+    _say(f"decode ffn T={T} k={k} E={E} d={d} F={F} bits={bits} {kind} {extras}")
+    rng = np.random.default_rng(T * 5 + E + bits + len(kind))
+    x = rng.standard_normal((T, d)).astype(np.float16).astype(np.float32)
+    w1 = (rng.standard_normal((E, d, F)) * 0.05).astype(np.float32)
+    w2 = (rng.standard_normal((E, F, d)) * 0.05).astype(np.float32)
+    idx = _routing(kind, T, k, E, rng)
+    if "pruned" in extras:
+        idx[rng.choice(T, size=7, replace=False)] = E
+    scale = rng.uniform(0.1, 1.0, (T, k)).astype(np.float32)
+    scale[idx == E] = 0.0
+    ob1 = ob2 = b1 = b2 = None
+    if "bias" in extras:
+        ob1 = rng.standard_normal((E, F)).astype(np.float16).astype(np.float32) * 0.1
+        ob2 = rng.standard_normal((E, d)).astype(np.float16).astype(np.float32) * 0.1
+        b1, b2 = to_dev(ob1, torch.float16), to_dev(ob2, torch.float16)
+    act = "gelu" if "gelu" in extras else "relu"
+    q1, s1 = oracle.quantize(w1, bits, 0)
+    q2, s2 = oracle.quantize(w2, bits, 0)
+    perm_src_o, inv_perm_o, off_o = oracle.permute(idx, E)
+    active = int(off_o[E])
+    y_o = np.zeros((T * k, d), dtype=np.float32)
+    y_o[:active] = oracle.grouped_ffn(oracle.gather_rows(x, perm_src_o[:active], k), off_o, q1, s1, q2, s2, 0, oracle.F16,
+                                      ob1, ob2, activation=B.ACTIVATIONS[act])
+    out_o = oracle.combine(y_o, inv_perm_o, scale, T, k, active_rows=active)
+    _, ds1, p1 = B.moe_quantize_experts(to_dev(w1, torch.float32), bits, 0, want_canon=False)
+    _, ds2, p2 = B.moe_quantize_experts(to_dev(w2, torch.float32), bits, 0, want_canon=False)
+    assert B.moe_grouped_ffn_wq_gated_supported(T, k, E, d, F, bits, 0, torch.float16) == 2
+    xd, idx_d, scale_d = to_dev(x, torch.float16), to_dev(idx, torch.int32), to_dev(scale, torch.float32)
+    out1, ps, ip, of = B.moe_grouped_ffn_wq_gated(xd, idx_d, E, d, F, bits, 0, p1, ds1, p2, ds2, b1, b2, expert_scale=scale_d,
+                                                  activation=act)
+    assert B.load().moe_last_ffn_kernels().decode() == "decode_ffn_kernel"
+    out2 = B.moe_grouped_ffn_wq_gated(xd, idx_d, E, d, F, bits, 0, p1, ds1, p2, ds2, b1, b2, expert_scale=scale_d, activation=act)[0]
+    torch.cuda.synchronize()
+    assert np.array_equal(of.cpu().numpy(), off_o)
+    assert np.array_equal(ps.cpu().numpy(), perm_src_o) and np.array_equal(ip.cpu().numpy(), inv_perm_o)
+    got = out1.cpu().numpy()
+    assert np.array_equal(got, out2.cpu().numpy())
+    assert not got[(idx == E).all(axis=1)].any()                # pruned tokens: exactly zero
+    max_abs, rel = error_metrics(got, out_o)
+    _say(f"   rows per expert up to {int(np.diff(off_o[:E + 1]).max())}, active {active} of {T * k}; max_abs={max_abs:.3e} rel_l2={rel:.3e}")
+    assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
+
+
 def test_gated_ffn_refuses_other_sizes():
     _say("gated ffn: what the fused permutation does not take is refused")
     assert not B.moe_grouped_ffn_wq_gated_supported(512, 1, 8, 1024, 4096, 4, 0, torch.float16)      # more than 256 assignments
