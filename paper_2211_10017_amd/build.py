@@ -11,6 +11,10 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmoe_wq.so")
 OBJ = os.path.join(HERE, "_build")
+# The same library with every hand-counted wait for direct-to-LDS loads replaced by a wait for all loads
+# (-DMOE_WAIT_ALL_LOADS): only the translation units of the tiled kernels differ.  tests/ compare the two.
+LIB_WAITALL = os.path.join(HERE, "libmoe_wq_waitall.so")
+TILED = [s for s in ("moe_ffn_tiled_4_f16.hip", "moe_ffn_tiled_4_bf16.hip", "moe_ffn_tiled_8_f16.hip", "moe_ffn_tiled_8_bf16.hip")]
 
 SOURCES = ["moe_errors.hip", "moe_quantize.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip", "moe_ffn_tiled.hip", "moe_ffn_tiled_4_f16.hip", "moe_ffn_tiled_4_bf16.hip",
            "moe_ffn_tiled_8_f16.hip", "moe_ffn_tiled_8_bf16.hip", "moe_ffn_stream.hip", "moe_ffn_decode.hip",
@@ -28,9 +32,10 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, variant: str = "") -> str:
+    obj = os.path.join(OBJ, src.replace(".hip", variant + ".o"))
+    extra = ["-DMOE_WAIT_ALL_LOADS"] if variant else []
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -45,8 +50,12 @@ def build_library(jobs: int = 8) -> str:
     """Compile every source and link the shared library; always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        objs = list(pool.map(_compile, SOURCES))
+        plain = pool.map(_compile, SOURCES)
+        waitall = pool.map(lambda s: _compile(s, "_waitall"), TILED)
+        objs, objs_waitall = list(plain), dict(zip(TILED, waitall))
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    other = [objs_waitall.get(src, obj) for src, obj in zip(SOURCES, objs)]
+    subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_WAITALL, *other])
     return LIB
 
 

@@ -208,12 +208,21 @@ __device__ inline void load_to_lds16(const void *src, uint16_t *dst)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(l) : "memory", "m0");
 }
 
-// s_waitcnt vmcnt(N) alone (the other counters' fields say "no wait")
+// s_waitcnt vmcnt(N) alone (the other counters' fields say "no wait").
+// Built with MOE_WAIT_ALL_LOADS every such wait is for ALL outstanding loads: slower, but free of any
+// assumption about how many loads the compiler issues after a direct-to-LDS load.  The library is built
+// a second time that way (libmoe_wq_waitall.so) and a GPU test compares the two builds bit for bit, so a
+// compiler that merges, splits or reorders one of the counted loads shows up as a failing test, not as
+// silently stale rows in LDS.
 template <int N>
 __device__ inline void wait_loads()
 {
     static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+#ifdef MOE_WAIT_ALL_LOADS
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+#else
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+#endif
 }
 
 // Inclusive prefix sum over the 64 lanes in the VALU's data-parallel primitives: shifts by 1, 2, 4
