@@ -60,13 +60,16 @@ def build_library(jobs: int = 8) -> str:
 
 
 def build_ceilings() -> str:
-    """Compile the stand-alone microbenchmark of the chip's achievable ceilings (microbench/ceilings)."""
-    src = os.path.join(HERE, "microbench", "ceilings.hip")
-    exe = os.path.join(HERE, "microbench", "ceilings")
+    """Compile the stand-alone study programs under microbench/: the chip's achievable ceilings and the
+    time-stamped decode kernel."""
     flags = [f for f in HIPCC_FLAGS if f != "-fPIC"]
-    res = subprocess.run([_hipcc(), *flags, src, "-o", exe], capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed for ceilings.hip:\n" + res.stderr)
+    exe = ""
+    for name, extra in (("ceilings", []), ("decode_timeline", [os.path.join(CSRC, "moe_errors.hip")])):
+        src = os.path.join(HERE, "microbench", name + ".hip")
+        exe = os.path.join(HERE, "microbench", name)
+        res = subprocess.run([_hipcc(), *flags, src, *extra, "-o", exe], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed for %s.hip:\n%s" % (name, res.stderr))
     return exe
 
 

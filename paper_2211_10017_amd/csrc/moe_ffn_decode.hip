@@ -31,7 +31,13 @@ namespace moe {
 
 constexpr int kDecWaves = 16;            // wavefronts per workgroup
 constexpr int kDecThreads = kDecWaves * 64;
-constexpr int kDecRing = 8;              // weight fragment blocks in flight per wavefront
+#ifndef MOE_DEC_RING
+#define MOE_DEC_RING 8
+#endif
+#ifndef MOE_DEC_AUX
+#define MOE_DEC_AUX 2
+#endif
+constexpr int kDecRing = MOE_DEC_RING;   // weight fragment blocks in flight per wavefront
 constexpr int kDecFit = 16;              // rows of an expert per pass (one 16-row matrix tile)
 constexpr int kDecRowPad = 8;            // halfs of padding per LDS row: rows start 4 banks apart
 constexpr int kDecChunk = 32 * kDecWaves;   // channels of d_ff per item
@@ -59,7 +65,7 @@ __device__ inline __amdgpu_buffer_rsrc_t dec_stream_rsrc(const uint8_t *base, ui
 }
 __device__ inline uint4 dec_ring_load(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t block_off)
 {
-    const dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, block_off, 2 /* nt */);
+    const dec_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, block_off, MOE_DEC_AUX /* 2 = nt */);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 

@@ -58,6 +58,32 @@ __global__ __launch_bounds__(256, 2) void read_regions(const uint4 *__restrict__
     if (acc == 0x12345678u) out[0] = acc;
 }
 
+// A resident grid that reads 128 MiB in one launch: every wavefront streams UNITS regions of 16 KB, one after the
+// other (region u of all wavefronts together is one contiguous range, as the two weight matrices of a decode step
+// are), through a ring of RING 16-byte-per-lane loads that is refilled block by block.  The refill's address is made
+// to depend on the block just consumed, so that the loads stay in ring order.
+template <int UNITS, int RING>
+__global__ __launch_bounds__(256, 2) void read_resident(const uint4 *p, uint32_t *out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t nw = (size_t)gridDim.x * 4, w = (size_t)blockIdx.x * 4 + wave;
+    const uint4 *base = p + w * 16 * 64 + lane;
+    uint4 ring[RING];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < RING; ++i) ring[i] = base[(size_t)i * 64];
+#pragma unroll
+    for (int g = 0; g < UNITS * 16; ++g) {
+        const uint4 v = ring[g % RING];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+        uint32_t z;
+        asm volatile("v_and_b32 %0, 0, %1" : "=v"(z) : "v"(v.x));      // an opaque zero that depends on the block's data
+        const int n = g + RING;
+        if (n < UNITS * 16) ring[g % RING] = base[((size_t)(n / 16) * nw * 16 + (n % 16)) * 64 + z];
+    }
+    if (acc == 0x12345678u) out[0] = acc;
+}
+
 __global__ __launch_bounds__(256, 2) void mfma_loop(const half8_t *__restrict__ in, float *out, int iters)
 {
     const half8_t a = in[threadIdx.x], b = in[256 + threadIdx.x];
@@ -110,6 +136,21 @@ int main()
                                (const uint4 *)((const char *)buf + (size_t)(i % 16) * per_launch), kb, sink);
         });
         printf("hbm read, %d KB region per wavefront (%d wavefronts), 64 MiB per launch: %.1f us per launch, %.0f GB/s\n", kb, waves, s * 1e6, per_launch / s / 1e9);
+    }
+    {
+        const size_t big = (size_t)128 << 20;
+        auto at = [&](int i) { return (const uint4 *)((const char *)buf + (size_t)(i % 8) * big); };
+        double s = timed(32, [&](int i) {
+            hipLaunchKernelGGL(read_regions, dim3(1024), dim3(256), 0, 0, (const uint4 *)((const char *)at(i)), 16, sink);
+            hipLaunchKernelGGL(read_regions, dim3(1024), dim3(256), 0, 0, (const uint4 *)((const char *)at(i) + per_launch), 16, sink);
+        });
+        printf("hbm read, 128 MiB in two launches of 4096 wavefronts x 16 KB: %.1f us per pair, %.0f GB/s\n", s * 1e6, big / s / 1e9);
+        s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<4, 16>), dim3(512), dim3(256), 0, 0, at(i), sink); });
+        printf("hbm read, 128 MiB in one launch, 2048 resident wavefronts (8 per CU) x 4 regions of 16 KB, ring of 16: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
+        s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<2, 16>), dim3(1024), dim3(256), 0, 0, at(i), sink); });
+        printf("hbm read, 128 MiB in one launch, 4096 resident wavefronts (16 per CU) x 2 regions of 16 KB, ring of 16: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
+        s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<2, 8>), dim3(1024), dim3(256), 0, 0, at(i), sink); });
+        printf("hbm read, 128 MiB in one launch, 4096 resident wavefronts (16 per CU) x 2 regions of 16 KB, ring of 8: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
     }
     {
         const double s = timed(4, [&](int) {
