@@ -72,7 +72,8 @@ def measured_traffic(workload: str, kernels: str):
 
 def box_peaks(torch, binding):
     """The peaks re-derived from what the box reports (CUs x 4096 fp16 flop per clock x engine
-    clock; memory clock x 2 transfers x bus width), printed beside the published constants."""
+    clock; memory bus width x pin rate, the pin rate of HBM3E being four transfers per reported
+    memory clock: 8 Gbit/s at the 2000 MHz this chip reports), printed beside the published constants."""
     p = torch.cuda.get_device_properties(0)
     info = binding.moe_device_info()
     cus, clk, mclk, bus = info["compute_units"], info["engine_clock_khz"], info["memory_clock_khz"], info["memory_bus_bits"]
@@ -84,7 +85,7 @@ def box_peaks(torch, binding):
     if cus and clk:
         out["mfma_f16_tflops_derived"] = cus * 4096 * clk * 1e3 / 1e12
     if mclk and bus:
-        out["hbm_gbs_derived"] = mclk * 1e3 * 2 * bus / 8 / 1e9
+        out["hbm_gbs_derived"] = mclk * 1e3 * 4 * bus / 8 / 1e9
     return out
 
 
