@@ -240,7 +240,9 @@ int moe_grouped_ffn_wq_routed(const void *x, int act_dtype, const int32_t *perm_
  *   workgroup per compute unit streams every active expert's W1 and W2 once (fc1, activation and
  *   fc2 per 512-channel slice of d_ff, h staying on chip) and leaves fp32 partial sums of y in the
  *   workspace; a small second launch adds the slices in a fixed order, applies the channel scale,
- *   bias and gate scale and writes out.  No atomics on this path.
+ *   bias and gate scale and writes out.  No atomics on this path.  (For timing studies y_perm may
+ *   be NULL on this path: the second launch is then left out and the partial sums stay in the
+ *   workspace.)
  * moe_grouped_ffn_wq_gated_supported returns 0 when a call with these sizes is not taken
  * (it then returns MOE_ERR_UNSUPPORTED and launches nothing), 1 when it is taken with
  * expert_scale = NULL, 2 when expert_scale may be given too.  Taken: fp16 activations,

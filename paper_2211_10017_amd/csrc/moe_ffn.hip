@@ -130,7 +130,10 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
                     int32_t *offsets_out = nullptr)
 {
     using namespace moe;
-    if (!expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || (R != 0 && (!x_perm || !y_perm)))
+    // (y_perm may be NULL only on the decode kernel's path, where it means "leave out the slice reduction")
+    const bool partial_only = !y_perm && gate_idx && expert_scale && act_dtype == MOE_F16 && group_size == 0 &&
+                              moe::decode_ffn_supports(R, E, d, F, bits);
+    if (!expert_offsets || !w1_packed || !s1 || !w2_packed || !s2 || (R != 0 && (!x_perm || (!y_perm && !partial_only))))
         return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: NULL pointer");
     if (R < 0 || E <= 0 || d <= 0 || F <= 0 || max_rows_per_expert < 0)
         return fail(MOE_ERR_INVALID_ARG, "moe_grouped_ffn_wq: R >= 0, max_rows_per_expert >= 0 and E, d, F > 0 required");

@@ -352,7 +352,7 @@ static int launch_decode(const DecodeArgs &p, int grid, hipStream_t s)
     const int lds = kDecFit * (K1 + kDecRowPad) * 2 + kDecFit * (kDecChunk + kDecRowPad) * 2;
     hipLaunchKernelGGL((decode_ffn_kernel<BITS, NB1, TS, NBC>), dim3(grid), dim3(kDecThreads), lds, s, p);
     int rc = check_launch("moe_grouped_ffn_wq_gated (decode kernel)");
-    if (rc) return rc;
+    if (rc || !p.out) return rc;                // (no output buffer: the partial sums are all the caller wants)
     hipLaunchKernelGGL(decode_reduce_kernel, dim3(p.n_assign / p.gate_k), dim3(256), 0, s, p);
     return check_launch("moe_grouped_ffn_wq_gated (slice reduction)");
 }

@@ -49,6 +49,7 @@ class MoEExpertLayer:
         self.ws_ffn = torch.empty(B.moe_grouped_ffn_wq_workspace_bytes(R, d, F, E, act_dtype),
                                   dtype=torch.uint8, device=dev)
         self._plans = {}
+        self._bare = {}
         # large batches: the row gather (and for k = 1 the un-permute and gate scale) run inside
         # the GEMMs instead of as copies of their own
         self.routed = bool(fuse_routing) and B.moe_grouped_ffn_wq_routed_supported(R, E, T, d, F, bits, group_size, act_dtype)
@@ -85,6 +86,21 @@ class MoEExpertLayer:
 
     def ffn(self, x, finished=None):
         self._step("moe_grouped_ffn_wq", x, finished)
+
+    def ffn_streaming_kernel_only(self, x, finished=None):
+        """The decode path's streaming kernel without its slice reduction (the gated call with a NULL output), for
+        timing that kernel alone.  Raises MoeError where the FFN call does not take the decode kernel."""
+        fn, args, what = [c for c in self._plan(x, finished) if c[2].startswith("moe_grouped_ffn_wq")][0]
+        if what != "moe_grouped_ffn_wq_gated":
+            raise B.MoeError("ffn_streaming_kernel_only: this layer does not run the gated FFN call")
+        bare = self._bare.get(id(args))
+        if bare is None:
+            if len(self._bare) > 256:
+                self._bare.clear()
+            bare = self._bare[id(args)] = (args, args[:18] + (None,) + args[19:])      # (keeps args alive: id stays unique)
+        rc = fn(*bare[1])
+        if rc != 0:
+            B._check(rc, what)
 
     def combine(self, x, finished=None):
         self._step("moe_combine", x, finished)       # nothing to do when fc2 stored the output itself

@@ -534,6 +534,37 @@ def test_decode_ffn_matches_oracle(T, k, E, d, F, bits, kind, extras):
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
 
+def test_decode_kernel_alone_leaves_a_full_call_unchanged():
+    """The gated call with a NULL output (the decode kernel without its slice reduction, which bench.py times) is
+    accepted only where the decode kernel runs, and a full call after it gives the same bits as before it."""
+    from paper_2211_10017_amd import MoEExpertLayer
+    _say("decode kernel alone: NULL output accepted on the decode path only")
+    T, k, E, d, F = 64, 2, 32, 1024, 1024
+    rng = np.random.default_rng(77)
+    layer = MoEExpertLayer(T, d, F, E, k, 4)
+    for e in range(E):
+        layer.load_expert(1, e, to_dev((rng.standard_normal((d, F)) * 0.05).astype(np.float32), torch.float32))
+        layer.load_expert(2, e, to_dev((rng.standard_normal((F, d)) * 0.05).astype(np.float32), torch.float32))
+    layer.wg.copy_(to_dev(rng.standard_normal((d, E)).astype(np.float32), torch.float16))
+    x = to_dev(rng.standard_normal((T, d)).astype(np.float32), torch.float16)
+    before = layer.forward(x).clone()
+    assert B.load().moe_last_ffn_kernels().decode() == "decode_ffn_kernel"
+    layer.out.fill_(7.0)
+    layer.ffn_streaming_kernel_only(x)
+    torch.cuda.synchronize()
+    assert bool((layer.out == 7.0).all())                       # no reduction ran: the output buffer is untouched
+    after = layer.forward(x)
+    torch.cuda.synchronize()
+    assert torch.equal(before, after)
+    other = MoEExpertLayer(T, d, 1088, E, k, 4)                  # F not a multiple of 512: the streaming pair, not the decode kernel
+    other.w1_packed.zero_(); other.w2_packed.zero_(); other.s1.zero_(); other.s2.zero_()
+    other.wg.copy_(layer.wg)
+    other.forward(x)
+    with pytest.raises(B.MoeError):
+        other.ffn_streaming_kernel_only(x)
+    torch.cuda.synchronize()
+
+
 def test_gated_ffn_refuses_other_sizes():
     _say("gated ffn: what the fused permutation does not take is refused")
     assert not B.moe_grouped_ffn_wq_gated_supported(512, 1, 8, 1024, 4096, 4, 0, torch.float16)      # more than 256 assignments
