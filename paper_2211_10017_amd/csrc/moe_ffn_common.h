@@ -58,6 +58,7 @@ struct DecodeArgs {
     float *out;                 // [T, d] fp32 layer output
     int32_t *perm_src_out, *inv_perm_out, *offsets_out;
     int items1;                 // workgroup items (set by the launcher)
+    int early_ring;             // an item requests its first weights before it knows the expert's row count (set by the launcher)
 };
 constexpr int kDecMaxExperts = 4096;
 bool decode_ffn_supports(int n_assign, int E, int d, int F, int bits);

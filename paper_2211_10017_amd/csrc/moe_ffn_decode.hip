@@ -83,7 +83,7 @@ __device__ inline void swap_rows(uint32_t &a, uint32_t &b)
 
 // BITS: weight width.  NB1: fragment blocks of a W1 slab (its whole K range, d_model).  TS: W2 slabs per
 // wavefront (d_model / 512).  NBC: fragment blocks of a W2 slab inside one d_ff slice of 512 rows.
-template <int BITS, int NB1, int TS, int NBC>
+template <int BITS, int NB1, int TS, int NBC, bool EARLY>
 __global__ __launch_bounds__(kDecThreads, 1) void decode_ffn_kernel(DecodeArgs p)
 {
     constexpr int FK = BITS == 4 ? 64 : 32;             // K values per fragment block
@@ -144,19 +144,38 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_ffn_kernel(DecodeArgs p
     const int koct = ((lane >> 4) & 1) * 16 + (lane >> 5) * 8;
 
     const int C = F / kDecChunk;                        // items per expert
+    const uint32_t lane_off = (uint32_t)lane * 16u;
+    // this wavefront's slab of W1 in item `it` (whole K range)
+    auto w1_slab = [&](int it) {
+        return p.w1 + (size_t)(it / C) * packed_bytes_per_expert(K1, F, BITS) + (size_t)((it % C) * kDecWaves + wave) * NB1 * kFragBytes;
+    };
+    // EARLY (the launcher's choice where nearly every expert has rows): an item's first ring is requested before the
+    // expert's row count is known (the count needs the gate's indices and two barriers; the weights need neither):
+    // for the workgroup's first item at once, for a further item when the item before it has used up its stream.
+    // Should the expert turn out empty, this one ring (a quarter of the item's stream) was read in vain.  Past the
+    // last item the descriptor has no extent: the same eight loads, no traffic, so that the count of loads in flight
+    // does not depend on the path taken.
+    auto prime = [&](int it) {
+        const __amdgpu_buffer_rsrc_t r1e = dec_stream_rsrc(w1_slab(min(it, p.items1 - 1)), it < p.items1 ? NB1 * kFragBytes : 0);
+        dec_static_for<0, kDecRing>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            W[i] = dec_ring_load(r1e, lane_off, i * kFragBytes);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    if constexpr (EARLY) prime(blk);
     for (int it = blk; it < p.items1; it += G) {
         const int e = it / C, c = it % C;
         int count, lower, rank, prank;
         bool mine, pruned;
-        expert_counts(e, count, lower, rank, prank, mine, pruned);
         // this wavefront's weight stream: its slab of W1 (whole K range), then the slice's rows of its TS slabs of W2
         // (the bases are the same for the whole wavefront, so they live in scalar registers; a lane adds 16 bytes x its number)
-        const uint8_t *w1b = p.w1 + (size_t)e * packed_bytes_per_expert(K1, F, BITS) + (size_t)(c * kDecWaves + wave) * NB1 * kFragBytes;
+        const uint8_t *w1b = w1_slab(it);
+        expert_counts(e, count, lower, rank, prank, mine, pruned);
         const uint8_t *w2b = p.w2 + (size_t)e * packed_bytes_per_expert(F, K1, BITS) +
                              ((size_t)(wave * TS) * (F / FK) + (size_t)c * NBC) * kFragBytes;
         const size_t slab2 = (size_t)(F / FK) * kFragBytes;             // bytes between consecutive slabs of W2
-        const uint32_t lane_off = (uint32_t)lane * 16u;
-        // an expert without rows costs no weight traffic: its descriptors have no extent (loads return zero
+        // an expert without rows costs no (further) weight traffic: its descriptors have no extent (loads return zero
         // without touching memory) and the item ends below
         const __amdgpu_buffer_rsrc_t r1 = dec_stream_rsrc(w1b, count ? NB1 * kFragBytes : 0);
         __amdgpu_buffer_rsrc_t r2[TS];
@@ -176,7 +195,7 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_ffn_kernel(DecodeArgs p
                 __builtin_amdgcn_sched_barrier(0);
             });
         };
-        issue_ring();
+        if constexpr (!EARLY) issue_ring();
         if (c == 0) {                           // the first item of an expert writes the expert's part of the index arrays
             if (tid == 0) {
                 p.offsets_out[e] = lower;
@@ -192,7 +211,10 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_ffn_kernel(DecodeArgs p
                 p.perm_src_out[r] = a_id;
             }
         }
-        if (count == 0) continue;
+        if (count == 0) {
+            if constexpr (EARLY) prime(it + G);
+            continue;
+        }
         if (mine) s_tok[rank] = a_tok;
         const int n1 = c * kDecChunk + wave * 32 + (lane & 15);        // this lane's fc1 channels: n1, n1 + 16
         const float cs0 = __half2float(p.s1[(size_t)e * F + n1]), cs1 = __half2float(p.s1[(size_t)e * F + n1 + 16]);
@@ -301,6 +323,7 @@ __global__ __launch_bounds__(kDecThreads, 1) void decode_ffn_kernel(DecodeArgs p
             }
             if (z0 + kDecFit < count) __syncthreads();      // LDS rows are free for the next pass
         }
+        if constexpr (EARLY) prime(it + G);
     }
     MOE_DEC_STAMP(7);
 }
@@ -350,7 +373,8 @@ static int launch_decode(const DecodeArgs &p, int grid, hipStream_t s)
     constexpr int FK = BITS == 4 ? 64 : 32;
     constexpr int K1 = NB1 * FK;
     const int lds = kDecFit * (K1 + kDecRowPad) * 2 + kDecFit * (kDecChunk + kDecRowPad) * 2;
-    hipLaunchKernelGGL((decode_ffn_kernel<BITS, NB1, TS, NBC>), dim3(grid), dim3(kDecThreads), lds, s, p);
+    if (p.early_ring) hipLaunchKernelGGL((decode_ffn_kernel<BITS, NB1, TS, NBC, true>), dim3(grid), dim3(kDecThreads), lds, s, p);
+    else hipLaunchKernelGGL((decode_ffn_kernel<BITS, NB1, TS, NBC, false>), dim3(grid), dim3(kDecThreads), lds, s, p);
     int rc = check_launch("moe_grouped_ffn_wq_gated (decode kernel)");
     if (rc || !p.out) return rc;                // (no output buffer: the partial sums are all the caller wants)
     hipLaunchKernelGGL(decode_reduce_kernel, dim3(p.n_assign / p.gate_k), dim3(256), 0, s, p);
@@ -388,6 +412,9 @@ int launch_decode_ffn(const DecodeArgs &q, int bits, hipStream_t s)
 {
     DecodeArgs p = q;
     p.items1 = p.E * (p.F / kDecChunk);
+    // three or more assignments per expert: under uniform routing at most one expert in twenty is empty, and the
+    // early ring of such an expert is a quarter of its weights
+    p.early_ring = p.n_assign >= 3 * p.E;
     const int grid = decode_ffn_grid(p.items1);
     if (bits == 4) return launch_decode<4, 16, 2, 8>(p, grid, s);
     return launch_decode<8, 16, 1, 16>(p, grid, s);

@@ -483,6 +483,9 @@ def _routing(kind, T, k, E, rng):
     (64, 2, 32, 1024, 4096, 4, "uniform", ""),                  # the decode workload's shape
     (64, 2, 32, 1024, 4096, 4, "one_hot_expert", ""),           # 64 rows in one expert: four passes; the rest one or two rows
     (30, 2, 32, 1024, 4096, 4, "few_experts", "pruned"),        # 27 experts without rows, pruned tokens
+    (64, 2, 32, 1024, 4096, 4, "few_experts", "pruned"),        # the same with four assignments per expert: the weights are requested
+                                                                # before the row counts are known, for 27 experts in vain
+    (128, 2, 80, 1024, 2048, 4, "uniform", ""),                 # early requests and 320 items: some workgroups take two
     (64, 2, 32, 512, 2048, 8, "uniform", "bias gelu"),          # 8-bit weights, biases, GELU
     (1, 1, 64, 1024, 1024, 4, "uniform", ""),                   # a single row
     (128, 2, 136, 1024, 1024, 4, "uniform", ""),                # 272 items: some workgroups take two
