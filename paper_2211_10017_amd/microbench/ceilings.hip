@@ -62,11 +62,13 @@ __global__ __launch_bounds__(256, 2) void read_regions(const uint4 *__restrict__
 // other (region u of all wavefronts together is one contiguous range, as the two weight matrices of a decode step
 // are), through a ring of RING 16-byte-per-lane loads that is refilled block by block.  The refill's address is made
 // to depend on the block just consumed, so that the loads stay in ring order.
-template <int UNITS, int RING>
-__global__ __launch_bounds__(256, 2) void read_resident(const uint4 *p, uint32_t *out)
+// THREADS = 1024 is the decode kernel's own launch shape: one workgroup of sixteen wavefronts per compute unit, all of
+// them started at once.
+template <int UNITS, int RING, int THREADS = 256>
+__global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void read_resident(const uint4 *p, uint32_t *out)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const size_t nw = (size_t)gridDim.x * 4, w = (size_t)blockIdx.x * 4 + wave;
+    const size_t nw = (size_t)gridDim.x * (THREADS / 64), w = (size_t)blockIdx.x * (THREADS / 64) + wave;
     const uint4 *base = p + w * 16 * 64 + lane;
     uint4 ring[RING];
     uint32_t acc = 0;
@@ -151,6 +153,10 @@ int main()
         printf("hbm read, 128 MiB in one launch, 4096 resident wavefronts (16 per CU) x 2 regions of 16 KB, ring of 16: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
         s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<2, 8>), dim3(1024), dim3(256), 0, 0, at(i), sink); });
         printf("hbm read, 128 MiB in one launch, 4096 resident wavefronts (16 per CU) x 2 regions of 16 KB, ring of 8: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
+        s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<2, 8, 512>), dim3(512), dim3(512), 0, 0, at(i), sink); });
+        printf("hbm read, 128 MiB in one launch, 512 workgroups of 8 wavefronts x 2 regions of 16 KB, ring of 8: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
+        s = timed(32, [&](int i) { hipLaunchKernelGGL((read_resident<2, 8, 1024>), dim3(256), dim3(1024), 0, 0, at(i), sink); });
+        printf("hbm read, 128 MiB in one launch, 256 workgroups of 16 wavefronts (one per CU, the decode kernel's shape) x 2 regions of 16 KB, ring of 8: %.1f us, %.0f GB/s\n", s * 1e6, big / s / 1e9);
     }
     {
         const double s = timed(4, [&](int) {

@@ -1,8 +1,9 @@
 // Timeline of the decode kernel (moe_ffn_decode.hip) on the decode workload's shape (64 tokens, top-2, 32 experts,
 // d_model 1024, d_ff 4096, int4): the kernel is compiled into this program with its time-stamp hook switched on, every
-// workgroup records the chip's constant 100 MHz clock at four points, and the program prints, over the workgroups, when
-// each point was reached, plus the time per call (kernel + slice reduction) of back-to-back calls that cycle through
-// 1 GiB of weight copies.  A study tool for the measurements quoted in the design notes; not used by the library.
+// workgroup records the chip's constant 100 MHz clock at four points (the time at which the last of its sixteen
+// wavefronts got there), and the program prints, over the workgroups, when each point was reached, plus the time per
+// call (kernel + slice reduction) of back-to-back calls that cycle through 1 GiB of weight copies.  A study tool for
+// the measurements quoted in the design notes; not used by the library.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -11,7 +12,7 @@
 #include <algorithm>
 __device__ unsigned long long *g_trace;
 #define MOE_DEC_STAMP_INIT unsigned long long *const dec_trace = g_trace
-#define MOE_DEC_STAMP(slot) do { if (threadIdx.x == 0 && dec_trace) dec_trace[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
+#define MOE_DEC_STAMP(slot) do { if ((threadIdx.x & 63) == 0 && dec_trace) atomicMax(&dec_trace[blockIdx.x * 16 + (slot)], (unsigned long long)wall_clock64()); } while (0)
 #include "../csrc/moe_ffn_decode.hip"
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); exit(1); } } while (0)
 using namespace moe;
@@ -53,6 +54,7 @@ int main(int argc, char **argv)
     printf("decode kernel, back to back: %.2f us per launch (%.0f GB/s on %.1f MB)\n", ms / reps * 1e3, 2.0 * wbytes / (ms / reps * 1e-3) / 1e9, 2.0 * wbytes / 1e6);
     // one traced launch
     CK(hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &trace, sizeof(trace)));
+    CK(hipMemset(trace, 0, 256 * 16 * 8));
     launch(3);
     CK(hipDeviceSynchronize());
     std::vector<unsigned long long> tr(256 * 16);
