@@ -9,16 +9,18 @@
 
 namespace moe {
 
-// Per-row power-of-two normalisation of bf16 activations: pow.x = 2^-p brings the row's
-// largest magnitude into [2^14, 2^15) so that every element converts to FP16 without
-// overflow and with its 8-bit significand intact; pow.y = 2^p undoes it after the GEMM.
-__global__ __launch_bounds__(256) void row_pow_kernel(const uint16_t *__restrict__ a, int R, int K,
-                                                      float2 *__restrict__ row_pow)
+// bf16 rows -> FP16 rows scaled by a power of two per row: pow.x = 2^-p brings the row's largest magnitude
+// into [2^14, 2^15), so that every element converts to FP16 without overflow; the GEMM takes the result like
+// FP16 rows (straight from memory into LDS) and multiplies its output rows by pow.y = 2^p.  A value keeps its 8-bit significand unless it is more than 2^-28 below the row's largest, where FP16
+// runs out of exponent.  `out` may be `in`: a lane reads what it converts before it writes it, and the row's
+// largest magnitude is known before the first write.
+__global__ __launch_bounds__(256) void rows_to_f16_kernel(const uint16_t *in, uint16_t *out, int R, int K, float2 *__restrict__ row_pow)
 {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= R) return;
-    const uint4 *row = reinterpret_cast<const uint4 *>(a + (size_t)r * K);
+    const uint4 *row = reinterpret_cast<const uint4 *>(in + (size_t)r * K);
+    uint4 *dst = reinterpret_cast<uint4 *>(out + (size_t)r * K);
     uint32_t amax = 0;
     for (int v = lane; v < K / 8; v += 64) {
         const uint4 q = row[v];
@@ -30,22 +32,31 @@ __global__ __launch_bounds__(256) void row_pow_kernel(const uint16_t *__restrict
         }
     }
     for (int off = 32; off > 0; off >>= 1) amax = max(amax, (uint32_t)__shfl_xor((int)amax, off));
-    if (lane == 0) {
-        int ex = (int)(amax >> 7);                 // biased exponent of the largest magnitude
-        if (ex == 255) ex = 141;                   // inf/nan rows: factor 1 (the result is nan anyway)
-        int fe = 268 - ex;                         // biased exponent of 2^(14 - (ex - 127))
-        fe = min(max(fe, 1), 253);
-        row_pow[r] = make_float2(__uint_as_float((uint32_t)fe << 23), __uint_as_float((uint32_t)(254 - fe) << 23));
+    int ex = (int)(amax >> 7);                     // biased exponent of the largest magnitude
+    if (ex == 255) ex = 141;                       // inf/nan rows: factor 1 (the result is nan anyway)
+    int fe = 268 - ex;                             // biased exponent of 2^(14 - (ex - 127))
+    fe = min(max(fe, 1), 253);
+    const float down = __uint_as_float((uint32_t)fe << 23);
+    if (lane == 0) row_pow[r] = make_float2(down, __uint_as_float((uint32_t)(254 - fe) << 23));
+    for (int v = lane; v < K / 8; v += 64) {
+        const uint4 q = row[v];
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const half2_t h = {(_Float16)(__uint_as_float(w[i] << 16) * down), (_Float16)(__uint_as_float(w[i] & 0xffff0000u) * down)};
+            o[i] = h2_bits(h);
+        }
+        dst[v] = make_uint4(o[0], o[1], o[2], o[3]);
     }
 }
 
 struct FfnWorkspace {
-    size_t h_off, pow_x_off, pow_h_off, partial_off, total;
+    size_t h_off, pow_x_off, pow_h_off, x16_off, partial_off, total;
 };
 
 static FfnWorkspace ffn_workspace(int R, int d, int F, int act_dtype)
 {
-    (void)d;
     FfnWorkspace w;
     size_t o = 0;
     w.h_off = o;
@@ -54,6 +65,8 @@ static FfnWorkspace ffn_workspace(int R, int d, int F, int act_dtype)
     if (act_dtype == MOE_BF16) o += round_up((size_t)R * sizeof(float2), 256);
     w.pow_h_off = o;
     if (act_dtype == MOE_BF16) o += round_up((size_t)R * sizeof(float2), 256);
+    w.x16_off = o;                               // bf16 rows: x converted to scaled FP16 (h is converted in place)
+    if (act_dtype == MOE_BF16) o += round_up((size_t)R * d * 2, 256);
     w.partial_off = o;                           // decode kernel: partial sums of y per d_ff slice
     if (R <= kGatedMaxAssign && F % 512 == 0) o += round_up(decode_ffn_partial_bytes(R, d, F), 256);
     w.total = o < 256 ? 256 : o;
@@ -95,6 +108,8 @@ static GemmKernel choose_kernel(int R, int E, int max_rows, int K, int N, int bi
     return GEMM_TILED;
 }
 
+// bf: the rows were bf16 (they come in converted to scaled FP16, with their factors in g.row_pow, which only the
+// tiled kernel applies)
 static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows, hipStream_t s)
 {
     using namespace moe;
@@ -106,7 +121,7 @@ static int run_gemm(moe::GemmArgs g, int bits, int smode, bool bf, int max_rows,
     // Everything else runs in the tiled kernel, experts with a handful of rows included: their tiles skip
     // the row blocks that hold no rows and stream the weights as fast as the streaming kernel would
     // (sending them there in a launch of their own measured 2-25 % slower on skewed loads).
-    return launch_tiled_gemm(g, bits, smode, bf, s);
+    return launch_tiled_gemm(g, bits, smode, s);
 }
 
 // true when a call with these sizes runs both GEMMs in the tiled kernel (the only kernel that takes
@@ -178,7 +193,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     // activations and group scales the weights go in as an exact two-term FP16 sum, because h
     // is rounded to 8 bits afterwards and a 2^-11 weight rounding would show through.
     GemmArgs g1{};
-    g1.a = (const uint16_t *)x_perm; g1.row_pow = pow_x; g1.offsets = expert_offsets;
+    g1.a = (const uint16_t *)x_perm; g1.row_pow = bf ? pow_x : nullptr; g1.offsets = expert_offsets;
     g1.wq = (const uint8_t *)w1_packed; g1.scales = (const __half *)s1; g1.bias = (const __half *)b1;
     g1.out = h; g1.E = E; g1.R = R; g1.K = d; g1.N = F; g1.g = grouped ? group_size : d;
     g1.out_dtype = act_dtype; g1.act = activation;
@@ -188,10 +203,12 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
         g1.perm_src_out = perm_src_out; g1.inv_perm_out = inv_perm_out; g1.offsets_out = offsets_out;
         if (expert_scale) { g1.zero_out = (float *)y_perm; g1.zero_count = (long)(R / k) * d; }   // fc2 adds into it
     }
-    if (bf) {
-        hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, R, d, pow_x);
-        int rc = check_launch("moe_grouped_ffn_wq (row scale x)");
+    if (bf) {           // bf16 rows: converted to power-of-two scaled FP16 rows first, then the GEMM of FP16 rows
+        uint16_t *x16 = (uint16_t *)(wsb + ws.x16_off);
+        hipLaunchKernelGGL(rows_to_f16_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)x_perm, x16, R, d, pow_x);
+        int rc = check_launch("moe_grouped_ffn_wq (x to scaled FP16)");
         if (rc) return rc;
+        g1.a = x16;
     }
     // (groups of 128: exact codes, group sums folded in fp32; other group sizes: the two-term form)
     const int smode1 = !grouped ? SCALE_CHANNEL : !bf ? SCALE_GROUP : group_size == 128 ? SCALE_GROUP_ACC : SCALE_GROUP_SPLIT;
@@ -200,7 +217,7 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
 
     // fc2: y = h @ deq(W2) + b2
     GemmArgs g2 = g1;
-    g2.a = (const uint16_t *)h; g2.row_pow = pow_h;
+    g2.a = (const uint16_t *)h; g2.row_pow = bf ? pow_h : nullptr;
     g2.wq = (const uint8_t *)w2_packed; g2.scales = (const __half *)s2; g2.bias = (const __half *)b2;
     g2.out = y_perm; g2.K = F; g2.N = d; g2.g = grouped ? group_size : F;
     g2.out_dtype = y_dtype; g2.act = MOE_ACT_NONE;
@@ -211,9 +228,9 @@ static int ffn_impl(const void *x_perm, int act_dtype, const int32_t *expert_off
     } else if (expert_scale) {
         g2.out_dst = perm_src; g2.out_scale = expert_scale;
     }
-    if (bf) {
-        hipLaunchKernelGGL(row_pow_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)h, R, F, pow_h);
-        rc = check_launch("moe_grouped_ffn_wq (row scale h)");
+    if (bf) {           // h, which fc1 rounded to bf16 (A13), in place
+        hipLaunchKernelGGL(rows_to_f16_kernel, dim3((R + 3) / 4), dim3(256), 0, s, (const uint16_t *)h, (uint16_t *)h, R, F, pow_h);
+        rc = check_launch("moe_grouped_ffn_wq (h to scaled FP16)");
         if (rc) return rc;
     }
     return run_gemm(g2, bits, grouped ? SCALE_GROUP : SCALE_CHANNEL, bf, max_rows, s);

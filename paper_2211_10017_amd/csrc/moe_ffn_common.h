@@ -67,11 +67,11 @@ int launch_decode_ffn(const DecodeArgs &p, int bits, hipStream_t s);
 
 constexpr int kGatedMaxAssign = 256;    // assignments the fused permutation takes: one per thread of a block
 
-int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s);
-void launch_tiled_4_f16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
-void launch_tiled_4_bf16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
-void launch_tiled_8_f16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
-void launch_tiled_8_bf16(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, hipStream_t s);
+void launch_tiled_4(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_4_exact(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_8(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
+void launch_tiled_8_exact(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s);
 int launch_stream_gemm(const GemmArgs &p, int bits, int smode, int max_rows, hipStream_t s);
 bool stream_gemm_supports(int K, int bits, int smode);
 int stream_gemm_fit_rows(int K);

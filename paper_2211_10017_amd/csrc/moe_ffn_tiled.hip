@@ -4,7 +4,7 @@
 
 namespace moe {
 
-int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStream_t s)
+int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, hipStream_t s)
 {
     // row-tile height from the mean rows per expert (the offsets themselves stay on the device)
     const int mean = (p.R + p.E - 1) / p.E;
@@ -36,10 +36,9 @@ int launch_tiled_gemm(const GemmArgs &p, int bits, int smode, bool abf16, hipStr
     const long wgs = (slots * ncol + kXcds - 1) / kXcds * kXcds;   // upper bound of the work items, whole rounds of XCDs
     if (wgs > 0x7fffffffL) return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: %ld workgroups exceed one launch", wgs);
     dim3 grid((unsigned)wgs);
-    if ((smode == SCALE_GROUP_ACC || smode == SCALE_GROUP_SPLIT) && !abf16)
-        return fail(MOE_ERR_UNSUPPORTED, "moe_grouped_ffn_wq: the exact group-scale forms are built for bf16 rows only");
-    if (bits == 4) (abf16 ? launch_tiled_4_bf16 : launch_tiled_4_f16)(q, smode, tm, grid, s);
-    else (abf16 ? launch_tiled_8_bf16 : launch_tiled_8_f16)(q, smode, tm, grid, s);
+    const bool exact = smode == SCALE_GROUP_ACC || smode == SCALE_GROUP_SPLIT;
+    if (bits == 4) (exact ? launch_tiled_4_exact : launch_tiled_4)(q, smode, tm, grid, s);
+    else (exact ? launch_tiled_8_exact : launch_tiled_8)(q, smode, tm, grid, s);
     return check_launch("moe_grouped_ffn_wq (gemm)");
 }
 

@@ -19,7 +19,7 @@ constexpr int kLdsRow = 64;              // halfs per LDS row: one K step, no pa
                                          // fragment reads conflict-free and keeps a wavefront's 64 chunks contiguous
 constexpr int kTN = 2;                   // 32-channel tiles per wavefront
 
-template <int BITS, int SMODE, bool ABF16, int TM>
+template <int BITS, int SMODE, int TM>
 __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 {
     constexpr int BM = 32 * TM;
@@ -54,13 +54,11 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     const int a_row = threadIdx.x >> 3, a_pos = (threadIdx.x & 7) * 8;
     const int a_seg = ((threadIdx.x & 7) ^ ((threadIdx.x >> 4) & 7)) * 8;
     const uint16_t *a_ptr[TM];
-    float a_down[TM];
 #pragma unroll
     for (int m = 0; m < TM; ++m) {
         const int r = row0 + min(a_row + 32 * m, rows - 1);      // clamped: always a valid row
         const int rs = p.a_src ? p.a_src[r] / p.a_div : r;       // gather fused into the A loads
         a_ptr[m] = p.a + (size_t)rs * K + a_seg;
-        a_down[m] = ABF16 ? p.row_pow[r].x : 1.0f;
     }
     // B: fragment blocks of tile t are contiguous along K
     const uint8_t *w_e = p.wq + (size_t)e * packed_bytes_per_expert(K, N, BITS);
@@ -99,19 +97,14 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     // one step of MFMA work is shorter than that latency).  The tallest 8-bit tile has registers
     // for one set only and fetches one step ahead.
     constexpr int PF = (BITS == 8 && TM == 4) ? 1 : 2;
-    // FP16 rows need no conversion and go from global memory straight into the LDS stage (DMA):
-    // no staging registers, no LDS write instructions.  bf16 rows pass through registers.
-    constexpr bool DMA = !ABF16;
+    // The rows (FP16; bf16 rows arrive converted, see rows_to_f16_kernel) go from global memory straight into
+    // the LDS stage: no staging registers, no LDS write instructions.
     constexpr int LB = kTN * NW + (SMODE != SCALE_CHANNEL ? kTN : 0);   // loads of one load_b()
     auto dma_a = [&](int kb, uint16_t *stage, int m) {
         load_to_lds16(a_ptr[m] + kb * 64, stage + (32 * m + 8 * wave) * kLdsRow);
     };
-    uint4 ga[TM], gb[PF][kTN][NW];
+    uint4 gb[PF][kTN][NW];
     _Float16 gs[PF][kTN];
-    auto load_a = [&](int kb) {
-#pragma unroll
-        for (int m = 0; m < TM; ++m) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kb * 64);
-    };
     auto load_b = [&](int kb, auto slot_c) {
         constexpr int WS = decltype(slot_c)::value;
 #pragma unroll
@@ -124,13 +117,9 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     };
 
     const int live = (rows + 31) / 32;
-    if constexpr (DMA) {
 #pragma unroll
-        for (int m = 0; m < TM; ++m)
-            if (m < live) dma_a(0, lds_a[0], m);
-    } else {
-        load_a(0);
-    }
+    for (int m = 0; m < TM; ++m)
+        if (m < live) dma_a(0, lds_a[0], m);
     load_b(0, std::integral_constant<int, 0>{});
     if constexpr (PF == 2) load_b(min(1, nk - 1), std::integral_constant<int, 1>{});
     // Private copies of the steps being computed.  They are taken (and the loads of the next
@@ -154,26 +143,6 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             sc2[WS][t] = __builtin_bit_cast(_Float16, (uint16_t)opaque_copy((uint32_t)__builtin_bit_cast(uint16_t, gs[WS][t])));
         }
     };
-    // registers -> LDS stage (bf16 rows are scaled by a power of two into FP16 range)
-    auto write_a = [&](uint16_t *stage, int live_tiles) {
-#pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            if (m >= live_tiles) continue;
-            uint4 v = ga[m];
-            if (ABF16) {
-                uint32_t in[4] = {v.x, v.y, v.z, v.w}, o[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float f0 = __uint_as_float(in[q] << 16) * a_down[m];
-                    const float f1 = __uint_as_float(in[q] & 0xffff0000u) * a_down[m];
-                    const half2_t h = {(_Float16)f0, (_Float16)f1};
-                    o[q] = h2_bits(h);
-                }
-                v = make_uint4(o[0], o[1], o[2], o[3]);
-            }
-            *reinterpret_cast<uint4 *>(stage + (a_row + 32 * m) * kLdsRow + a_pos) = v;
-        }
-    };
     // One barrier per step, at its top: it publishes this step's stage (written during the
     // previous step) and tells that every wavefront has left the other stage, which is then
     // refilled at the end of the step, when its rows have had time to arrive; the arrival of
@@ -184,7 +153,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         uint16_t *stage = lds_a[SL];
         // this wavefront's share of the stage has landed once only the weight refills issued after
         // it (in the previous step) are still in flight
-        if constexpr (DMA) wait_loads<PF == 2 ? (SL == 1 ? 2 * LB : 0) : LB>();
+        wait_loads<PF == 2 ? (SL == 1 ? 2 * LB : 0) : LB>();
         __syncthreads();
         uint32_t (&raw)[kTN][NW * 4] = raw2[PF == 2 ? SL : 0];
         _Float16 (&sc)[kTN] = sc2[PF == 2 ? SL : 0];
@@ -200,8 +169,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
 #pragma unroll
                 for (int m = 0; m < TM; ++m)       // (row tiles past the expert's last row are neither loaded nor written)
                     if (m < LIVE && (TM == 1 ? j == 0 : (m < TM / 2) == (j == 0))) {
-                        if constexpr (!DMA) ga[m] = *reinterpret_cast<const uint4 *>(a_ptr[m] + kn * 64);
-                        else dma_a(kn, lds_a[1 - SL], m);     // the other stage: every wavefront has left it
+                        dma_a(kn, lds_a[1 - SL], m);          // the other stage: every wavefront has left it
                     }
             } else if constexpr (PF == 2) {
                 if constexpr (SL == 0) {
@@ -247,7 +215,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
         // MFMAs of step j are issued, so that the LDS latency passes under a full step of matrix
         // work; otherwise each fragment is read just before its MFMAs and the other wavefront of
         // the SIMD covers the wait.
-        constexpr bool PIPE = TM < 4 || !(SMODE == SCALE_GROUP_SPLIT || (SMODE == SCALE_GROUP && ABF16 && BITS == 4));
+        constexpr bool PIPE = TM < 4 || !(SMODE == SCALE_GROUP_SPLIT || false);
         uint32_t bw[2][kTN][4], bl[2][kTN][4];
         half8_t af[PIPE ? 2 : 1][TM];
         auto read_a = [&](int j, int m) {
@@ -286,11 +254,6 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
                     }
                 }
             }
-            if (!DMA && j == 3) {
-                __builtin_amdgcn_sched_barrier(0);
-                write_a(lds_a[1 - SL], LIVE);
-                __builtin_amdgcn_sched_barrier(0);
-            }
         }
         if constexpr (ACC && SL == 1) {                 // end of the group: acc += scale * accg
 #pragma unroll
@@ -317,12 +280,11 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
             }
         }
     };
-    if constexpr (!DMA) write_a(lds_a[0], live);
     if (TM == 1 || live == TM) k_loop(std::integral_constant<int, TM>{});
     else if (TM >= 4 && live == 3) k_loop(std::integral_constant<int, 3>{});
     else if (TM >= 2 && live == 2) k_loop(std::integral_constant<int, 2>{});
     else k_loop(std::integral_constant<int, 1>{});
-    if constexpr (DMA) wait_loads<0>();      // the last step's (unused) refill of the other stage must land before the block's LDS is given up
+    wait_loads<0>();      // the last step's (unused) refill of the other stage must land before the block's LDS is given up
 
     // ---- epilogue: scale (per channel), bias, activation, store.  acc[m][t][i] is row
     // 32*m + 8*(i/4) + 4*(lane/32) + i%4 of the tile, channel lane%32 of tile t.
@@ -332,7 +294,7 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     // odd lane channels (n-1, n) of the second.
     auto finish = [&](float a, int rl, float cs, float bias) {
         float v = a * cs;
-        if (ABF16) v *= p.row_pow[row0 + min(rl, rows - 1)].y;
+        if (p.row_pow) v *= p.row_pow[row0 + min(rl, rows - 1)].y;     // rows that went in scaled by a power of two (bf16 rows)
         v += bias;
         v = activate(v, p.act);
         if (p.out_dst) v *= s_scale[min(rl, rows - 1)];         // gate scale of the fused un-permute
@@ -384,30 +346,27 @@ __global__ __launch_bounds__(256, 2) void grouped_gemm_kernel(GemmArgs p)
     else store_tiles(_Float16{});
 }
 
-template <int BITS, int SMODE, bool ABF16>
+template <int BITS, int SMODE>
 static void launch_tm(const GemmArgs &p, int tm, dim3 grid, hipStream_t s)
 {
-    if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 1>), grid, dim3(256), 0, s, p);
-    else if (tm == 2) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 2>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, ABF16, 4>), grid, dim3(256), 0, s, p);
+    if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, 1>), grid, dim3(256), 0, s, p);
+    else if (tm == 2) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, 2>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SMODE, 4>), grid, dim3(256), 0, s, p);
 }
 
-// All kernels of one weight width and one activation dtype (one translation unit each, so that they
-// compile side by side).
-template <int BITS, bool ABF16>
+// All kernels of one weight width and one kind of scale mode (one translation unit each, so that they
+// compile side by side): EXACT = the two forms that keep the group scales out of the FP16 weights.
+template <int BITS, bool EXACT>
 static void launch_tiled_variants(const GemmArgs &p, int smode, int tm, dim3 grid, hipStream_t s)
 {
-    if (smode == SCALE_CHANNEL) {
-        launch_tm<BITS, SCALE_CHANNEL, ABF16>(p, tm, grid, s);
-    } else if (smode == SCALE_GROUP) {
-        launch_tm<BITS, SCALE_GROUP, ABF16>(p, tm, grid, s);
-    } else if constexpr (ABF16) {
-        if (smode == SCALE_GROUP_ACC) {                    // row tiles of at most 64 rows
-            if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, true, 1>), grid, dim3(256), 0, s, p);
-            else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, true, 2>), grid, dim3(256), 0, s, p);
-        } else {
-            launch_tm<BITS, SCALE_GROUP_SPLIT, true>(p, tm, grid, s);
-        }
+    if constexpr (!EXACT) {
+        if (smode == SCALE_CHANNEL) launch_tm<BITS, SCALE_CHANNEL>(p, tm, grid, s);
+        else launch_tm<BITS, SCALE_GROUP>(p, tm, grid, s);
+    } else if (smode == SCALE_GROUP_ACC) {                 // row tiles of at most 64 rows
+        if (tm == 1) hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, 1>), grid, dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((grouped_gemm_kernel<BITS, SCALE_GROUP_ACC, 2>), grid, dim3(256), 0, s, p);
+    } else {
+        launch_tm<BITS, SCALE_GROUP_SPLIT>(p, tm, grid, s);
     }
 }
 

@@ -1,4 +1,4 @@
-"""The tiled grouped GEMM sends fp16 activation rows from global memory straight into LDS and waits for
+"""The tiled grouped GEMM sends its activation rows (fp16, or bf16 converted to scaled fp16 beforehand) from global memory straight into LDS and waits for
 them with a hand-counted `s_waitcnt vmcnt(n)`, n = the weight loads issued after them.  The library is
 built a second time (libmoe_wq_waitall.so) with every such wait replaced by a wait for ALL loads, which
 needs no counting.  If a compiler change ever merged, split or reordered one of the counted loads, the
@@ -33,7 +33,7 @@ def _ffn(lib, x, off, R, E, d, F, bits, g, p1, s1, p2, s2, y_dtype):
     return y, lib.moe_last_ffn_kernels().decode()
 
 
-@pytest.mark.parametrize("rows,d,F,bits,g,y_dt", [
+@pytest.mark.parametrize("rows,d,F,bits,g,y_dt,x_dt", [(*c, torch.float16) for c in [
     ([20, 31, 5, 0, 17], 192, 256, 4, 0, torch.float16),            # 32-row tiles; 3 and 4 K steps (odd, even)
     ([20, 31, 5, 0, 17], 192, 256, 8, 64, torch.float32),
     ([60, 50, 33, 5], 192, 320, 4, 64, torch.float32),              # 64-row tiles, last tiles with one live row tile; 3 and 5 K steps
@@ -41,15 +41,21 @@ def _ffn(lib, x, off, R, E, d, F, bits, g, p1, s1, p2, s2, y_dtype):
     ([270, 257, 130, 20], 2112, 2176, 4, 0, torch.float16),         # 128-row tiles (3, 3, 2 + 1 and 1 live row tiles); 33 and 34 K steps
     ([270, 257, 130, 20], 2112, 2176, 4, 64, torch.float32),        # ... with a scale per group
     ([300, 290, 270], 2112, 2112, 8, 0, torch.float16),             # tallest 8-bit tiles: weights fetched one step ahead
-    ([300, 290, 270], 2112, 2112, 8, 64, torch.float32)])
-def test_counted_waits_equal_waiting_for_all_loads(rows, d, F, bits, g, y_dt):
-    print(f"wait guard rows={rows} d={d} F={F} bits={bits} g={g} y={y_dt}", flush=True)
+    ([300, 290, 270], 2112, 2112, 8, 64, torch.float32)]] + [
+    # bf16 rows: fc1 keeps the group scales out of the weights (group sums folded in fp32 for groups of 128, two-term weights otherwise)
+    ([20, 31, 5, 0, 17], 256, 384, 4, 128, torch.float32, torch.bfloat16),      # 32-row tiles, group sums
+    ([60, 50, 33, 5], 384, 256, 8, 128, torch.float32, torch.bfloat16),         # 64-row tiles, group sums
+    ([270, 257, 130, 20], 2176, 2304, 4, 128, torch.float32, torch.bfloat16),   # taller experts: group sums stay on 64-row tiles
+    ([60, 50, 33, 5], 192, 320, 4, 64, torch.float32, torch.bfloat16),          # two-term weights, 64-row tiles
+    ([270, 257, 130, 20], 2112, 2176, 8, 64, torch.float32, torch.bfloat16)])   # two-term weights, 128-row tiles
+def test_counted_waits_equal_waiting_for_all_loads(rows, d, F, bits, g, y_dt, x_dt):
+    print(f"wait guard rows={rows} d={d} F={F} bits={bits} g={g} y={y_dt} x={x_dt}", flush=True)
     assert os.path.exists(WAITALL), "libmoe_wq_waitall.so is built by paper_2211_10017_amd.build together with the library"
     rng = np.random.default_rng(sum(rows) + d + bits + g)
     E = len(rows)
     off = to_dev(np.concatenate([[0], np.cumsum(rows)]).astype(np.int32), torch.int32)
     R = int(sum(rows))
-    x = to_dev(rng.standard_normal((R, d)).astype(np.float32), torch.float16)
+    x = to_dev(rng.standard_normal((R, d)).astype(np.float32), x_dt)
     w1 = to_dev((rng.standard_normal((E, d, F)) * 0.05).astype(np.float32), torch.float32)
     w2 = to_dev((rng.standard_normal((E, F, d)) * 0.05).astype(np.float32), torch.float32)
     _, s1, p1 = B.moe_quantize_experts(w1, bits, g, want_canon=False)
