@@ -162,8 +162,9 @@ int moe_permute(const int32_t *expert_idx, const void *x, int act_dtype, int T, 
  *   y_perm [R,d] in y_dtype (MOE_F16 | MOE_BF16 | MOE_F32)
  * Requires d % 64 == 0, F % 64 == 0, bits in {4,8}, group_size 0 or a multiple of 64 dividing
  * both d and F.
- * Workspace: h (R * F elements of act_dtype), the per-row factors of bf16 rows, and for decode-sized
- * batches (R <= 256) the partial sums moe_grouped_ffn_wq_gated keeps (F / 512 x R x d fp32).
+ * Workspace: h (R * F elements of act_dtype), for bf16 rows their per-row factors and x_perm converted to
+ * scaled FP16 (R * d elements), and for decode-sized batches (R <= 256) the partial sums
+ * moe_grouped_ffn_wq_gated keeps (F / 512 x R x d fp32).
  */
 size_t moe_grouped_ffn_wq_workspace_bytes(int R, int d, int F, int E, int act_dtype);
 int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_offsets, int R,
@@ -177,7 +178,7 @@ int moe_grouped_ffn_wq(const void *x_perm, int act_dtype, const int32_t *expert_
  * moe_grouped_ffn_wq for callers that cannot allocate device memory or carry a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
  * and same results (bit for bit: the same kernels run) as moe_grouped_ffn_wq without the
- * workspace pair; h (and the per-row factors of bf16 rows) live in a fixed array of
+ * workspace pair; h (and what bf16 rows need: their factors and the converted x_perm) live in a fixed array of
  * moe_grouped_ffn_wq_noalloc_max_bytes() = 8 MiB inside the library's own device memory, which
  * every GPU the library is used on holds until the process ends.  The call allocates and frees
  * nothing (its first call on a device looks up the array's address, nothing more).
