@@ -14,7 +14,7 @@ OBJ = os.path.join(HERE, "_build")
 # The same library with every hand-counted wait for direct-to-LDS loads replaced by a wait for all loads
 # (-DMOE_WAIT_ALL_LOADS): only the translation units of the tiled kernels differ.  tests/ compare the two.
 LIB_WAITALL = os.path.join(HERE, "libmoe_wq_waitall.so")
-TILED = [s for s in ("moe_ffn_tiled_4.hip", "moe_ffn_tiled_4_exact.hip", "moe_ffn_tiled_8.hip", "moe_ffn_tiled_8_exact.hip")]
+TILED = ["moe_ffn_tiled_4.hip", "moe_ffn_tiled_4_exact.hip", "moe_ffn_tiled_8.hip", "moe_ffn_tiled_8_exact.hip"]
 
 SOURCES = ["moe_errors.hip", "moe_quantize.hip", "moe_gate.hip", "moe_permute.hip", "moe_ffn.hip", "moe_ffn_tiled.hip", "moe_ffn_tiled_4.hip", "moe_ffn_tiled_4_exact.hip",
            "moe_ffn_tiled_8.hip", "moe_ffn_tiled_8_exact.hip", "moe_ffn_stream.hip", "moe_ffn_decode.hip",

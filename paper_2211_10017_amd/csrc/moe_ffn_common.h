@@ -13,8 +13,8 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 enum { SCALE_CHANNEL = 0, SCALE_GROUP = 1, SCALE_GROUP_SPLIT = 2, SCALE_GROUP_ACC = 3 };
 
 struct GemmArgs {
-    const uint16_t *a;        // [R, K] fp16 or bf16 bit patterns
-    const float2 *row_pow;    // bf16 only: per row (2^-p, 2^p) normalisation factors
+    const uint16_t *a;        // [R, K] fp16 bit patterns (rows that were bf16 come converted, scaled by 2^-p per row)
+    const float2 *row_pow;    // null, or per row (2^-p, 2^p): the tiled kernel multiplies its output rows by 2^p
     const int32_t *offsets;   // [E+1]
     const uint8_t *wq;        // packed codes, [E] x packed_bytes_per_expert
     const __half *scales;     // [E, K/g, N]
