@@ -193,6 +193,37 @@ def test_grouped_ffn_matches_oracle(rows, d, F, bits, g, act, y_dt):
     assert max_abs <= MAX_ABS_TOL and rel <= REL_L2_TOL
 
 
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 0), (4, 64)])
+def test_grouped_ffn_bf16_rows_of_any_magnitude(bits, g):
+    """bf16 rows far outside the FP16 range (rows scaled by 2^-40 ... 2^40) and with elements down to 2^-30 of their
+    row's largest: every row goes into the GEMMs scaled by its own power of two and comes out scaled back.  Without
+    biases the layer is homogeneous in a row's scale, so each row is compared relative to its own size."""
+    _say(f"ffn bf16 rows of any magnitude bits={bits} g={g}")
+    rng = np.random.default_rng(11 + bits + g)
+    rows, d, F = [40, 100], 256, 256
+    E, R = len(rows), sum(rows)
+    off = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    row_scale = 2.0 ** (8 * (np.arange(R) % 11 - 5))
+    col_scale = 2.0 ** (-2.0 * (np.arange(d) % 16))
+    x = to_dev((rng.standard_normal((R, d)) * row_scale[:, None] * col_scale[None, :]).astype(np.float32), torch.bfloat16)
+    w1 = (rng.standard_normal((E, d, F)) * 0.05).astype(np.float32)
+    w2 = (rng.standard_normal((E, F, d)) * 0.05).astype(np.float32)
+    _, s1, p1 = B.moe_quantize_experts(to_dev(w1, torch.float32), bits, g, want_canon=False)
+    _, s2, p2 = B.moe_quantize_experts(to_dev(w2, torch.float32), bits, g, want_canon=False)
+    q1, os1 = oracle.quantize(w1, bits, g)
+    q2, os2 = oracle.quantize(w2, bits, g)
+    y = B.moe_grouped_ffn_wq(x, to_dev(off, torch.int32), E, d, F, bits, g, p1, s1, p2, s2, y_dtype=torch.float32)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().astype(np.float64)
+    want = oracle.grouped_ffn(x.float().cpu().numpy(), off, q1, os1, q2, os2, g, oracle.BF16).astype(np.float64)
+    assert np.isfinite(got).all()
+    size = np.sqrt((want ** 2).sum(axis=1))
+    assert (size > 0).all() and size.max() / size.min() > 2.0 ** 70          # the rows really span the range
+    rel = np.sqrt(((got - want) ** 2).sum(axis=1)) / size
+    _say(f"   row sizes 2^{np.log2(size.min()):.0f} .. 2^{np.log2(size.max()):.0f}; worst relative L2 error of a row {rel.max():.3e}")
+    assert rel.max() <= 2 * REL_L2_TOL
+
+
 @pytest.mark.parametrize("rows,d,F,bits", [
     # a row bound of at most 64, but several row groups per expert and enough row tiles to fill the chip: the tiled kernel
     ([40, 37, 44, 40, 1, 40, 39, 40, 64, 40, 33, 40], 1024, 4096, 4),
